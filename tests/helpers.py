@@ -1,0 +1,30 @@
+"""Shared test plumbing: builds oracle models and inputs from the seeded generators."""
+import functools
+
+import numpy as np
+
+import synth
+from oracle import vlac_oracle as O
+
+
+def oracle_model(cfg, seed, gain_jitter=0.1, std=0.02, dtype=np.float64, cache_layers=True):
+    """Oracle Model over synth weights (bf16 values upcast)."""
+    def layer(l):
+        return {k: v.float().numpy() for k, v in
+                synth.make_layer(cfg, seed, l, std=std, gain_jitter=gain_jitter).items()}
+    if cache_layers:
+        layer = functools.lru_cache(maxsize=None)(layer)
+    head = {k: v.float().numpy() for k, v in
+            synth.make_head(cfg, seed, std=std, gain_jitter=gain_jitter).items()}
+    return O.Model(cfg, layer, head, dtype=dtype)
+
+
+def tiny_inputs(seed=0, H=112, patch=14, n_redraw=16, n_text=16, d_model=256, jitter=2):
+    """The tiny configuration's inputs: two frames, their visual token embeddings
+    (bf16-representable) and the text embeddings."""
+    prev, cur, redrawn = synth.frame_pair(H, H, patch, n_redraw, seed, jitter=jitter)
+    wp = synth.projection_matrix(d_model, patch, seed + 1)
+    txt = synth.round_bf16(synth.text_embeddings(n_text, d_model, seed + 2))
+    e_prev = np.concatenate([synth.round_bf16(synth.visual_embeddings(prev, patch, wp)), txt])
+    e_cur = np.concatenate([synth.round_bf16(synth.visual_embeddings(cur, patch, wp)), txt])
+    return prev, cur, redrawn, e_prev, e_cur
