@@ -1,0 +1,186 @@
+/*
+ * vlac: VLA-Cache sparse prefill for a Llama-style VLA decoder on MI355X (gfx950).
+ *
+ * C ABI of the library.  One control step of the method (arXiv 2502.02175) is
+ *   vlac_select_static   Alg. 1: which visual tokens may reuse last step's K/V
+ *   vlac_layer_ratio     Sec. 3.4: how many of them each decoder layer reuses
+ *   vlac_sparse_prefill  Alg. 2: decoder pass over the recomputed rows only
+ *   vlac_decode_action   Sec. 3.1 / Appendix: KV-cache decode of the other action tokens
+ *
+ * Conventions
+ *  - Every function returns 0 (VLAC_OK) or a negative vlac_status.  Nothing
+ *    throws, aborts or prints.  Arguments are validated on the host before any
+ *    GPU work is queued; a failed call queues nothing.
+ *  - "device" pointers are HIP device memory owned by the caller and only
+ *    borrowed for the call; "host" pointers are ordinary memory.  The library
+ *    owns only the opaque context (packed weights, workspace).
+ *  - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL =
+ *    the default stream) and must all use the same stream, or be ordered by the
+ *    caller.  Calls on one context must not overlap.
+ *  - Sequence layout of one stream: [L_v visual tokens in raster order over the
+ *    N x N patch grid][L_t text tokens], positions 0 .. L-1, L = L_v + L_t.
+ *    Action tokens decoded after the prefill take positions L, L+1, ...
+ *  - Index lists are int32.  bf16 means the upper 16 bits of an IEEE fp32.
+ */
+#ifndef VLAC_H
+#define VLAC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  VLAC_OK = 0,
+  VLAC_E_NULL = -1,   /* a required pointer is NULL */
+  VLAC_E_SHAPE = -2,  /* sizes inconsistent with each other or with the model */
+  VLAC_E_RANGE = -3,  /* a scalar or an index is out of its allowed range */
+  VLAC_E_STATE = -4,  /* call order: weights missing, cache of a stream never filled */
+  VLAC_E_HIP = -5,    /* the HIP runtime reported an error (see vlac_last_hip_error) */
+  VLAC_E_NOMEM = -6   /* device or host allocation failed */
+} vlac_status;
+
+typedef struct vlac_ctx vlac_ctx;
+
+/* Decoder shape (Sec. 3.1; Llama layout: RMSNorm, rotary embedding in the
+ * rotate-half pairing, grouped-query attention, SwiGLU feed-forward).
+ * Limits: head_dim is 64 or 128; d_model, n_q_heads*head_dim and d_ffn are
+ * multiples of 16; n_q_heads is a multiple of 4 and of n_kv_heads; vocab is a
+ * multiple of 32; max_seq is a multiple of 32 and at most 65536. */
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rms_eps, rope_base;
+  int32_t max_batch; /* streams (independent environments, each with its own KV cache) */
+  int32_t max_seq;   /* cache slots per stream: L + decoded action tokens, rounded up to 32 */
+} vlac_model_cfg;
+
+/* One decoder layer, device pointers, bf16, row-major [out_features, in_features]
+ * (y = x W^T).  wqkv rows: all query heads, then all key heads, then all value
+ * heads.  w_gate_up rows: the gate projection, then the up projection. */
+typedef struct {
+  const void* wqkv;      /* [(Hq + 2 Hkv) * hd, d] */
+  const void* wo;        /* [d, Hq * hd] */
+  const void* w_gate_up; /* [2 F, d] */
+  const void* w_down;    /* [d, F] */
+  const void* g_attn;    /* [d] RMSNorm gain before attention */
+  const void* g_ffn;     /* [d] RMSNorm gain before the feed-forward */
+} vlac_layer_w;
+
+const char* vlac_status_string(int status);
+
+/* Creates a context on the current HIP device and allocates its workspace.
+ * *out is set only on success. */
+int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out);
+int vlac_destroy(vlac_ctx* ctx);
+
+/* Last hipError_t seen by this context (0 = none), for VLAC_E_HIP. */
+int vlac_last_hip_error(const vlac_ctx* ctx);
+
+/* Copies one layer's weights into the context in the tiled order the matrix
+ * cores consume (the caller's buffers may be freed once the stream has run).
+ * All layers and the head must be set before any prefill. */
+int vlac_set_layer_weights(vlac_ctx* ctx, int layer, const vlac_layer_w* w, void* stream);
+/* g_final [d], w_head [vocab, d], embed [vocab, d] (token embedding table used
+ * by vlac_decode_action): device, bf16. */
+int vlac_set_head_weights(vlac_ctx* ctx, const void* g_final, const void* w_head,
+                          const void* embed, void* stream);
+
+/* Bytes of KV cache for max_batch streams.  The cache is one caller-owned device
+ * buffer; its internal order (K and V tiled per 32 positions for the matrix
+ * cores, K stored after the rotary embedding) is private to the library.
+ * It persists across control steps: it is the state Alg. 2 carries from t-1 to t. */
+size_t vlac_kv_cache_bytes(const vlac_model_cfg* cfg);
+
+/* Zero-fills stream b's part of the cache and marks it "never filled": the next
+ * prefill of that stream must be a full one.  Must be called once per stream
+ * before its first prefill (the kernels read whole 32-position tiles). */
+int vlac_reset_stream(vlac_ctx* ctx, int b, void* kv_cache, void* stream);
+
+/* Waits for `stream`, then reports whether any kernel of this context met an
+ * index it had to ignore (reuse index outside [0, L_v), count larger than the
+ * stride): VLAC_E_RANGE once, then cleared.  Kernels never act on such entries. */
+int vlac_check(vlac_ctx* ctx, void* stream);
+
+/* Alg. 1 (Sec. 3.2 Eq. sim, Eq. topk; Sec. 3.3 Eq. ptask, Eq. pfinal).
+ *
+ * frame_prev, frame_cur: device uint8 [B, H, W, 3] (frames t-1 and t).  H and W
+ * are multiples of `patch`; L_v = (H/patch) * (W/patch) <= 4096; patch <= 64.
+ * A patch is static iff cos(P_t, P_{t-1}) >= tau_num / tau_den, tested exactly in
+ * integers (0 <= tau_num <= tau_den, 1 <= tau_den < 2^31); two all-zero patches
+ * are static, exactly one all-zero patch is not.  Of the static patches the
+ * top_k most similar are kept (exact comparison, ties: lower index), 0 <= top_k <= L_v.
+ *
+ * attn_mean: device fp32 [n_layers, B, L_v], the out_attn_mean of the previous
+ * vlac_sparse_prefill (text-to-vision attention, mean over heads and text rows),
+ * or NULL to switch the task-relevance filter off.  layer_mask: host bytes
+ * [n_layers], non-zero = layer belongs to the set averaged over (NULL = all).
+ * The score S is that average (fp32, layers in ascending order).  The
+ * L_v - floor(tau_task * L_v) highest-scoring tokens (ties: lower index) are
+ * task-relevant and are removed from the reusable set.
+ *
+ * out_idx   device int32 [B, stride]: P_final, ascending, first out_count[b] valid
+ * out_order device int32 [B, stride]: the same set ordered by (S ascending,
+ *           index ascending), the order in which layers pick tokens to reuse
+ * out_count device int32 [B]
+ * out_relevance device fp32 [B, L_v] or NULL: S
+ * stride >= top_k. */
+int vlac_select_static(vlac_ctx* ctx, const uint8_t* frame_prev, const uint8_t* frame_cur,
+                       int B, int H, int W, int patch, int tau_num, int tau_den, int top_k,
+                       const float* attn_mean, const uint8_t* layer_mask, float tau_task,
+                       int32_t* out_idx, int32_t* out_order, int32_t* out_count,
+                       float* out_relevance, int stride, void* stream);
+
+/* Sec. 3.4, Eq. reuse_ratio: per stream, entropy E^l of attn_mean[l, b, :]
+ * normalised over the vision tokens, R^l = (E^{l-1} - E^l) / E^{l-1} (R^1 = 0;
+ * 0 when E^{l-1} = 0), alpha^l = clamp(gain_k * sum_{j<=l} R^j, 0, 1), made
+ * non-decreasing over l.
+ * reuse_count: device int32 [B] (out_count of vlac_select_static) or NULL.
+ * out_alpha: device fp32 [B, n_layers].
+ * out_layer_count: device int32 [B, n_layers] = floor(alpha^l * reuse_count[b])
+ * (fp32 product), or NULL; requires reuse_count. */
+int vlac_layer_ratio(vlac_ctx* ctx, const float* attn_mean, int B, int L_v, float gain_k,
+                     const int32_t* reuse_count, float* out_alpha, int32_t* out_layer_count,
+                     void* stream);
+
+/* Alg. 2 with the appendix's token-reuse mechanism (Eq. KV reuse in Sec. 4.1).
+ *
+ * embeds: device fp32 [B, L, d], the input embeddings of frame t, L = L_v + L_t.
+ * At layer l stream b reuses, untouched, the cached K/V of the first
+ * m = min(layer_count[b, l], reuse_count[b]) tokens of reuse_order[b, :] and
+ * recomputes all other rows (every text token always): RMSNorm, QKV, rotary
+ * embedding at the row's original position, K/V written in place into
+ * kv_cache, causal attention of the recomputed queries over the whole mixed
+ * cache, output projection, SwiGLU feed-forward.  m is made non-decreasing over
+ * l (a reused token has no hidden state to come back from).
+ *
+ * reuse_order: device int32 [B, stride]; reuse_count: device int32 [B], or both
+ * NULL for a full recompute (required for a stream after vlac_reset_stream).
+ * Entries outside [0, L_v) and repeated entries are ignored (see vlac_check).
+ * layer_count: device int32 [B, n_layers] or NULL (= reuse_count at every layer).
+ *
+ * out_attn_mean: device fp32 [n_layers, B, L_v] or NULL: this step's
+ *   text-to-vision attention statistic, input of the next step's selection.
+ * out_hidden: device fp32 [B, L, d] or NULL: hidden state after the final norm of
+ *   every row still recomputed at the last layer; other rows are left untouched.
+ * out_logits: device fp32 [B, vocab] or NULL: logits of position L-1.
+ * out_token: device int32 [B]: greedy first action token (ties: lower id). */
+int vlac_sparse_prefill(vlac_ctx* ctx, const float* embeds, int B, int L_v, int L_t,
+                        const int32_t* reuse_order, const int32_t* reuse_count, int stride,
+                        const int32_t* layer_count, void* kv_cache, float* out_attn_mean,
+                        float* out_hidden, float* out_logits, int32_t* out_token, void* stream);
+
+/* Greedy KV-cache decode of n_new further action tokens (Sec. 3.1; Appendix
+ * "Token Reuse Mechanism", last paragraph).  first_token: device int32 [B], the
+ * out_token of the prefill; it is embedded at position L, its successor at L+1, ...
+ * Requires L + n_new <= max_seq.  Cache positions >= L are scratch that the next
+ * control step overwrites.
+ * out_tokens: device int32 [B, n_new]; out_logits: device fp32 [B, n_new, vocab] or NULL. */
+int vlac_decode_action(vlac_ctx* ctx, int B, int L, int n_new, const int32_t* first_token,
+                       void* kv_cache, int32_t* out_tokens, float* out_logits, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VLAC_H */

@@ -1,0 +1,428 @@
+// C-ABI layer of vlac: argument validation, context and workspace management,
+// and the per-step launch sequences.  Semantics of every entry point are stated
+// in include/vlac.h.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "common.h"
+
+namespace {
+
+template <class T>
+hipError_t dalloc(T** p, size_t n) {
+  *p = nullptr;
+  return hipMalloc((void**)p, (n ? n : 1) * sizeof(T));
+}
+
+size_t frag_elems(int rows, int kpad) { return (size_t)round_up(rows, 32) * kpad; }
+
+size_t kv_elems_per_stream(const vlac_model_cfg& m) {
+  return (size_t)m.n_layers * 2 * m.n_kv_heads * m.max_seq * m.head_dim;
+}
+
+int check_cfg(const vlac_model_cfg* m) {
+  if (m->n_layers < 1 || m->n_layers > 512 || m->d_model < 32 || m->n_q_heads < 1 ||
+      m->n_kv_heads < 1 || m->d_ffn < 16 || m->vocab < 32 || m->max_batch < 1 || m->max_seq < 32)
+    return VLAC_E_RANGE;
+  if (m->head_dim != 64 && m->head_dim != 128) return VLAC_E_SHAPE;
+  if (m->d_model % 32 || m->d_ffn % 16 || m->vocab % 32 || m->max_seq % 32) return VLAC_E_SHAPE;
+  if (m->n_q_heads % 4 || m->n_q_heads % m->n_kv_heads) return VLAC_E_SHAPE;
+  if (m->max_seq > 65536 || m->max_batch > 32767) return VLAC_E_RANGE;
+  if (!(m->rms_eps > 0.f) || !(m->rope_base > 1.f)) return VLAC_E_RANGE;
+  return VLAC_OK;
+}
+
+void free_all(vlac_ctx* c) {
+  if (!c) return;
+  if (c->layers) {
+    for (int l = 0; l < c->cfg.n_layers; ++l) {
+      void* lw[] = {c->layers[l].wqkv, c->layers[l].wo, c->layers[l].wgu,
+                    c->layers[l].wdown, c->layers[l].g_attn, c->layers[l].g_ffn};
+      for (void* p : lw) (void)hipFree(p);
+    }
+    free(c->layers);
+  }
+  void* dev[] = {c->w_head, c->embed, c->g_final, c->rope_cos, c->rope_sin, c->h, c->xa, c->xf,
+                 c->qbuf, c->partial, c->counters, c->rows, c->n_rows, c->slot_off, c->rank,
+                 c->m_layer, c->n_rows_bl, c->statp, c->stat_counters, c->logits, c->tokens,
+                 c->dec_rows, c->terms, c->flags, c->relevance, c->errword, c->scratch_i};
+  for (void* p : dev) (void)hipFree(p);
+  free(c->layer_set); free(c->filled); free(c->was_reset);
+  free(c);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* vlac_status_string(int s) {
+  switch (s) {
+    case VLAC_OK: return "ok";
+    case VLAC_E_NULL: return "required pointer is NULL";
+    case VLAC_E_SHAPE: return "inconsistent sizes";
+    case VLAC_E_RANGE: return "value out of range";
+    case VLAC_E_STATE: return "call order / state";
+    case VLAC_E_HIP: return "HIP runtime error";
+    case VLAC_E_NOMEM: return "out of memory";
+    default: return "unknown status";
+  }
+}
+
+size_t vlac_kv_cache_bytes(const vlac_model_cfg* cfg) {
+  if (!cfg || check_cfg(cfg) != VLAC_OK) return 0;
+  return kv_elems_per_stream(*cfg) * cfg->max_batch * sizeof(bf16_t);
+}
+
+int vlac_last_hip_error(const vlac_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out) {
+  if (!cfg || !out) return VLAC_E_NULL;
+  const int rc = check_cfg(cfg);
+  if (rc != VLAC_OK) return rc;
+  vlac_ctx* ctx = (vlac_ctx*)calloc(1, sizeof(vlac_ctx));
+  if (!ctx) return VLAC_E_NOMEM;
+  ctx->cfg = *cfg;
+  const vlac_model_cfg& m = ctx->cfg;
+  ctx->q_dim = m.n_q_heads * m.head_dim;
+  ctx->kv_dim = m.n_kv_heads * m.head_dim;
+  ctx->qkv_dim = ctx->q_dim + 2 * ctx->kv_dim;
+  ctx->group = m.n_q_heads / m.n_kv_heads;
+  ctx->kpad_d = round_up(m.d_model, 64);
+  ctx->kpad_q = round_up(ctx->q_dim, 64);
+  ctx->kpad_f = round_up(m.d_ffn, 64);
+  ctx->max_rows = m.max_batch * m.max_seq;
+  ctx->layers = (LayerW*)calloc(m.n_layers, sizeof(LayerW));
+  ctx->layer_set = (uint8_t*)calloc(m.n_layers, 1);
+  ctx->filled = (uint8_t*)calloc(m.max_batch, 1);
+  ctx->was_reset = (uint8_t*)calloc(m.max_batch, 1);
+  if (!ctx->layers || !ctx->layer_set || !ctx->filled || !ctx->was_reset) {
+    free_all(ctx);
+    return VLAC_E_NOMEM;
+  }
+  hipError_t e = hipGetDevice(&ctx->device);
+  const int nl = m.n_layers, mb = m.max_batch, ms = m.max_seq, mr = ctx->max_rows;
+  const int kpad_x = ctx->kpad_d > ctx->kpad_q ? ctx->kpad_d : ctx->kpad_q;
+  ctx->partial_floats = (size_t)64 << 20;  // 256 MiB of split-K workspace
+  ctx->n_counters = 1 << 16;
+  ctx->stat_tt = ms / 32 + 1;
+#define A_(ptr, n) if (e == hipSuccess) e = dalloc(&ctx->ptr, (size_t)(n))
+  for (int l = 0; l < nl && e == hipSuccess; ++l) {
+    A_(layers[l].wqkv, frag_elems(ctx->qkv_dim, ctx->kpad_d));
+    A_(layers[l].wo, frag_elems(m.d_model, ctx->kpad_q));
+    A_(layers[l].wgu, frag_elems(2 * m.d_ffn, ctx->kpad_d));
+    A_(layers[l].wdown, frag_elems(m.d_model, ctx->kpad_f));
+    A_(layers[l].g_attn, m.d_model);
+    A_(layers[l].g_ffn, m.d_model);
+  }
+  A_(w_head, frag_elems(m.vocab, ctx->kpad_d));
+  A_(embed, (size_t)m.vocab * m.d_model);
+  A_(g_final, m.d_model);
+  A_(rope_cos, (size_t)ms * (m.head_dim / 2));
+  A_(rope_sin, (size_t)ms * (m.head_dim / 2));
+  A_(h, (size_t)mr * m.d_model);
+  A_(xa, frag_elems(mr, kpad_x));
+  A_(xf, frag_elems(mr, ctx->kpad_f));
+  A_(qbuf, frag_elems(mr, ctx->q_dim));
+  A_(partial, ctx->partial_floats);
+  A_(counters, ctx->n_counters);
+  A_(rows, (size_t)(nl + 1) * mr);
+  A_(n_rows, nl + 1);
+  A_(slot_off, (size_t)(nl + 1) * (mb + 1));
+  A_(rank, (size_t)mr);
+  A_(m_layer, (size_t)mb * nl);
+  A_(n_rows_bl, (size_t)mb * nl);
+  A_(statp, (size_t)mb * m.n_q_heads * ctx->stat_tt * ms);
+  A_(stat_counters, mb);
+  A_(logits, (size_t)mb * m.vocab);
+  A_(tokens, mb);
+  A_(dec_rows, (size_t)ms * mb + ms + (size_t)ms * (mb + 1));
+  A_(terms, (size_t)mb * 4096 * 3);
+  A_(flags, (size_t)mb * 4096);
+  A_(relevance, (size_t)mb * 4096);
+  A_(errword, 1);
+  A_(scratch_i, 64);
+#undef A_
+  if (e == hipSuccess) e = hipMemset(ctx->counters, 0, ctx->n_counters * sizeof(int));
+  if (e == hipSuccess) e = hipMemset(ctx->stat_counters, 0, mb * sizeof(int));
+  if (e == hipSuccess) e = hipMemset(ctx->errword, 0, sizeof(int));
+  // operand padding (rows of the last 32-row tile, K padding) must be finite: zero once
+  if (e == hipSuccess) e = hipMemset(ctx->xa, 0, frag_elems(mr, kpad_x) * sizeof(bf16_t));
+  if (e == hipSuccess) e = hipMemset(ctx->xf, 0, frag_elems(mr, ctx->kpad_f) * sizeof(bf16_t));
+  if (e == hipSuccess) e = hipMemset(ctx->qbuf, 0, frag_elems(mr, ctx->q_dim) * sizeof(bf16_t));
+  if (e == hipSuccess) {
+    // rotary table in fp64 on the host: angle = pos * base^(-2 i / hd)
+    const int half = m.head_dim / 2;
+    float* hc = (float*)malloc((size_t)ms * half * sizeof(float));
+    float* hs = (float*)malloc((size_t)ms * half * sizeof(float));
+    if (!hc || !hs) {
+      free(hc); free(hs); free_all(ctx);
+      return VLAC_E_NOMEM;
+    }
+    for (int p = 0; p < ms; ++p)
+      for (int i = 0; i < half; ++i) {
+        const double ang = (double)p * pow((double)m.rope_base, -2.0 * i / m.head_dim);
+        hc[(size_t)p * half + i] = (float)cos(ang);
+        hs[(size_t)p * half + i] = (float)sin(ang);
+      }
+    e = hipMemcpy(ctx->rope_cos, hc, (size_t)ms * half * sizeof(float), hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+      e = hipMemcpy(ctx->rope_sin, hs, (size_t)ms * half * sizeof(float), hipMemcpyHostToDevice);
+    free(hc); free(hs);
+  }
+  if (e == hipSuccess) e = (hipError_t)gemm_init();
+  if (e != hipSuccess) {
+    const bool oom = (e == hipErrorOutOfMemory);
+    free_all(ctx);
+    (void)hipGetLastError();
+    return oom ? VLAC_E_NOMEM : VLAC_E_HIP;
+  }
+  *out = ctx;
+  return VLAC_OK;
+}
+
+int vlac_destroy(vlac_ctx* ctx) {
+  if (!ctx) return VLAC_E_NULL;
+  (void)hipDeviceSynchronize();
+  free_all(ctx);
+  return VLAC_OK;
+}
+
+int vlac_set_layer_weights(vlac_ctx* ctx, int layer, const vlac_layer_w* w, void* stream) {
+  if (!ctx || !w) return VLAC_E_NULL;
+  if (layer < 0 || layer >= ctx->cfg.n_layers) return VLAC_E_RANGE;
+  if (!w->wqkv || !w->wo || !w->w_gate_up || !w->w_down || !w->g_attn || !w->g_ffn)
+    return VLAC_E_NULL;
+  const vlac_model_cfg& m = ctx->cfg;
+  hipStream_t st = (hipStream_t)stream;
+  LayerW& L = ctx->layers[layer];
+  launch_pack((const bf16_t*)w->wqkv, ctx->qkv_dim, m.d_model, L.wqkv, ctx->qkv_dim, ctx->kpad_d, 1,
+              ctx->q_dim, ctx->kv_dim, m.head_dim, st);
+  launch_pack((const bf16_t*)w->wo, m.d_model, ctx->q_dim, L.wo, m.d_model, ctx->kpad_q, 0, 0, 0, 0, st);
+  launch_pack((const bf16_t*)w->w_gate_up, 2 * m.d_ffn, m.d_model, L.wgu, 2 * m.d_ffn, ctx->kpad_d, 2,
+              m.d_ffn, 0, 0, st);
+  launch_pack((const bf16_t*)w->w_down, m.d_model, m.d_ffn, L.wdown, m.d_model, ctx->kpad_f, 0, 0, 0, 0, st);
+  launch_bf16_to_f32((const bf16_t*)w->g_attn, L.g_attn, m.d_model, st);
+  launch_bf16_to_f32((const bf16_t*)w->g_ffn, L.g_ffn, m.d_model, st);
+  VLAC_HIP(hipGetLastError());
+  ctx->layer_set[layer] = 1;
+  return VLAC_OK;
+}
+
+int vlac_set_head_weights(vlac_ctx* ctx, const void* g_final, const void* w_head, const void* embed,
+                          void* stream) {
+  if (!ctx || !g_final || !w_head || !embed) return VLAC_E_NULL;
+  const vlac_model_cfg& m = ctx->cfg;
+  hipStream_t st = (hipStream_t)stream;
+  launch_pack((const bf16_t*)w_head, m.vocab, m.d_model, ctx->w_head, m.vocab, ctx->kpad_d, 0, 0, 0, 0, st);
+  launch_bf16_to_f32((const bf16_t*)g_final, ctx->g_final, m.d_model, st);
+  VLAC_HIP(hipMemcpyAsync(ctx->embed, embed, (size_t)m.vocab * m.d_model * sizeof(bf16_t),
+                          hipMemcpyDeviceToDevice, st));
+  VLAC_HIP(hipGetLastError());
+  ctx->head_set = true;
+  return VLAC_OK;
+}
+
+int vlac_reset_stream(vlac_ctx* ctx, int b, void* kv_cache, void* stream) {
+  if (!ctx || !kv_cache) return VLAC_E_NULL;
+  if (b < 0 || b >= ctx->cfg.max_batch) return VLAC_E_RANGE;
+  const size_t bytes = kv_elems_per_stream(ctx->cfg) * sizeof(bf16_t);
+  VLAC_HIP(hipMemsetAsync((char*)kv_cache + (size_t)b * bytes, 0, bytes, (hipStream_t)stream));
+  ctx->filled[b] = 0;
+  ctx->was_reset[b] = 1;
+  return VLAC_OK;
+}
+
+int vlac_check(vlac_ctx* ctx, void* stream) {
+  if (!ctx) return VLAC_E_NULL;
+  int word = 0;
+  VLAC_HIP(hipMemcpyAsync(&word, ctx->errword, sizeof(int), hipMemcpyDeviceToHost, (hipStream_t)stream));
+  VLAC_HIP(hipStreamSynchronize((hipStream_t)stream));
+  if (word) {
+    VLAC_HIP(hipMemsetAsync(ctx->errword, 0, sizeof(int), (hipStream_t)stream));
+    VLAC_HIP(hipStreamSynchronize((hipStream_t)stream));
+    return VLAC_E_RANGE;
+  }
+  return VLAC_OK;
+}
+
+int vlac_select_static(vlac_ctx* ctx, const uint8_t* frame_prev, const uint8_t* frame_cur, int B,
+                       int H, int W, int patch, int tau_num, int tau_den, int top_k,
+                       const float* attn_mean, const uint8_t* layer_mask, float tau_task,
+                       int32_t* out_idx, int32_t* out_order, int32_t* out_count,
+                       float* out_relevance, int stride, void* stream) {
+  if (!ctx || !frame_prev || !frame_cur || !out_idx || !out_order || !out_count) return VLAC_E_NULL;
+  if (B < 1 || B > ctx->cfg.max_batch) return VLAC_E_RANGE;
+  if (patch < 1 || patch > 64 || H < 1 || W < 1) return VLAC_E_RANGE;
+  if (H % patch || W % patch) return VLAC_E_SHAPE;
+  const long L_v = (long)(H / patch) * (W / patch);
+  if (L_v > 4096) return VLAC_E_RANGE;
+  if (tau_den < 1 || tau_num < 0 || tau_num > tau_den) return VLAC_E_RANGE;
+  if (top_k < 0 || top_k > L_v) return VLAC_E_RANGE;
+  if (stride < top_k || stride < 1) return VLAC_E_SHAPE;
+  if (tau_task != tau_task) return VLAC_E_RANGE;  // NaN
+  int n_rel = 0;
+  if (attn_mean) {
+    // the L_v - floor(tau_task * L_v) highest-scoring tokens are task-relevant
+    const double keep = floor((double)tau_task * (double)L_v);
+    double nr = (double)L_v - keep;
+    n_rel = nr < 0 ? 0 : (nr > (double)L_v ? (int)L_v : (int)nr);
+  }
+  hipStream_t st = (hipStream_t)stream;
+  launch_patch_terms(frame_prev, frame_cur, B, H, W, patch, ctx->terms, st);
+  launch_select(ctx->terms, B, (int)L_v, tau_num, tau_den, top_k, attn_mean, ctx->cfg.n_layers,
+                layer_mask, n_rel, ctx->flags, ctx->relevance, out_idx, out_order, out_count,
+                out_relevance, stride, st);
+  VLAC_HIP(hipGetLastError());
+  return VLAC_OK;
+}
+
+int vlac_layer_ratio(vlac_ctx* ctx, const float* attn_mean, int B, int L_v, float gain_k,
+                     const int32_t* reuse_count, float* out_alpha, int32_t* out_layer_count,
+                     void* stream) {
+  if (!ctx || !attn_mean || !out_alpha) return VLAC_E_NULL;
+  if (out_layer_count && !reuse_count) return VLAC_E_NULL;
+  if (B < 1 || B > ctx->cfg.max_batch || L_v < 1 || L_v > 65536) return VLAC_E_RANGE;
+  if (gain_k != gain_k) return VLAC_E_RANGE;
+  launch_layer_ratio(attn_mean, ctx->cfg.n_layers, B, L_v, gain_k, reuse_count, out_alpha,
+                     out_layer_count, (hipStream_t)stream);
+  VLAC_HIP(hipGetLastError());
+  return VLAC_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+// One decoder layer over the rows of plane `rows` (count *n_rows <= rows_cap).
+void run_layer(vlac_ctx* c, int layer, int B, int rows_cap, int rows_cap_per_stream, int L_v, int L_t,
+               const float* resid_in, int resid_stride, const int* rows, const int* n_rows,
+               const int* slot_off, bf16_t* kv, float* out_attn_mean, hipStream_t st) {
+  const vlac_model_cfg& m = c->cfg;
+  const LayerW& W = c->layers[layer];
+  GemmEpi e;
+  memset(&e, 0, sizeof(e));
+  e.rows = rows;
+  e.rope_cos = c->rope_cos; e.rope_sin = c->rope_sin;
+  e.qbuf = c->qbuf;
+  e.kv = kv;
+  e.kv_stream_stride = kv_elems_per_stream(m);
+  e.kv_layer_off = (size_t)layer * 2 * m.n_kv_heads * m.max_seq * m.head_dim;
+  e.n_q_heads = m.n_q_heads; e.n_kv_heads = m.n_kv_heads; e.head_dim = m.head_dim;
+  e.max_seq = m.max_seq;
+  e.h = c->h; e.d_model = m.d_model;
+  e.xf = c->xf; e.kc_f = c->kpad_f / 16; e.d_ffn = m.d_ffn;
+
+  launch_rmsnorm_rows(resid_in, resid_stride, rows, n_rows, rows_cap, W.g_attn, m.rms_eps,
+                      m.d_model, c->xa, c->kpad_d / 16, st);
+  launch_gemm(c, EPI_QKV, W.wqkv, c->qkv_dim / 32, c->kpad_d, c->xa, n_rows, rows_cap, e, st);
+  launch_attention(c, layer, B, rows_cap_per_stream, L_v, L_t, rows, slot_off, kv, out_attn_mean, st);
+  e.resid_src = resid_in; e.resid_seq_stride = resid_stride;
+  launch_gemm(c, EPI_RESID, W.wo, m.d_model / 32, c->kpad_q, c->xa, n_rows, rows_cap, e, st);
+  launch_rmsnorm_rows(c->h, m.max_seq, rows, n_rows, rows_cap, W.g_ffn, m.rms_eps, m.d_model, c->xa,
+                      c->kpad_d / 16, st);
+  launch_gemm(c, EPI_SWIGLU, W.wgu, 2 * m.d_ffn / 32, c->kpad_d, c->xa, n_rows, rows_cap, e, st);
+  e.resid_src = c->h; e.resid_seq_stride = m.max_seq;
+  launch_gemm(c, EPI_RESID, W.wdown, m.d_model / 32, c->kpad_f, c->xf, n_rows, rows_cap, e, st);
+}
+
+// Final norm + output head + greedy token for the B rows of plane `rows`.
+void run_head(vlac_ctx* c, int B, const int* rows, const int* n_rows, float* logits,
+              size_t logits_stride, int32_t* out_token, int out_stride, int32_t* token_copy, hipStream_t st) {
+  const vlac_model_cfg& m = c->cfg;
+  GemmEpi e;
+  memset(&e, 0, sizeof(e));
+  e.rows = rows;
+  e.logits = logits; e.vocab = m.vocab; e.logits_stride = logits_stride;
+  launch_rmsnorm_rows(c->h, m.max_seq, rows, n_rows, B, c->g_final, m.rms_eps, m.d_model, c->xa,
+                      c->kpad_d / 16, st);
+  launch_gemm(c, EPI_LOGITS, c->w_head, m.vocab / 32, c->kpad_d, c->xa, n_rows, B, e, st);
+  launch_argmax(logits, logits_stride, B, m.vocab, out_token, out_stride, token_copy, st);
+}
+
+int weights_ready(const vlac_ctx* c) {
+  if (!c->head_set) return 0;
+  for (int l = 0; l < c->cfg.n_layers; ++l)
+    if (!c->layer_set[l]) return 0;
+  return 1;
+}
+
+}  // namespace
+
+extern "C" {
+
+int vlac_sparse_prefill(vlac_ctx* ctx, const float* embeds, int B, int L_v, int L_t,
+                        const int32_t* reuse_order, const int32_t* reuse_count, int stride,
+                        const int32_t* layer_count, void* kv_cache, float* out_attn_mean,
+                        float* out_hidden, float* out_logits, int32_t* out_token, void* stream) {
+  if (!ctx || !embeds || !kv_cache || !out_token) return VLAC_E_NULL;
+  if ((reuse_order == nullptr) != (reuse_count == nullptr)) return VLAC_E_NULL;
+  if (layer_count && !reuse_count) return VLAC_E_NULL;
+  const vlac_model_cfg& m = ctx->cfg;
+  if (B < 1 || B > m.max_batch) return VLAC_E_RANGE;
+  if (L_v < 0 || L_t < 0 || L_v + L_t < 1) return VLAC_E_RANGE;
+  const int L = L_v + L_t;
+  if (L > m.max_seq) return VLAC_E_SHAPE;
+  if (reuse_order && (stride < 1 || L_v < 1)) return VLAC_E_SHAPE;
+  if (!weights_ready(ctx)) return VLAC_E_STATE;
+  for (int b = 0; b < B; ++b) {
+    if (!ctx->was_reset[b]) return VLAC_E_STATE;
+    if (reuse_order && !ctx->filled[b]) return VLAC_E_STATE;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  const int nl = m.n_layers;
+  launch_plan(ctx, B, L_v, L_t, reuse_order, reuse_count, stride, layer_count, st);
+  const int rows_cap = B * L;
+  for (int l = 0; l < nl; ++l) {
+    const int* rows = ctx->rows + (size_t)l * ctx->max_rows;
+    run_layer(ctx, l, B, rows_cap, L, L_v, L_t, l == 0 ? embeds : ctx->h, l == 0 ? L : m.max_seq,
+              rows, ctx->n_rows + l, ctx->slot_off + (size_t)l * (m.max_batch + 1),
+              (bf16_t*)kv_cache, out_attn_mean, st);
+  }
+  if (out_hidden)
+    launch_final_hidden(ctx->h, m.max_seq, ctx->rows + (size_t)(nl - 1) * ctx->max_rows,
+                        ctx->n_rows + (nl - 1), rows_cap, ctx->g_final, m.rms_eps, m.d_model,
+                        out_hidden, L, st);
+  run_head(ctx, B, ctx->rows + (size_t)nl * ctx->max_rows, ctx->n_rows + nl,
+           out_logits ? out_logits : ctx->logits, (size_t)m.vocab, out_token, 1, nullptr, st);
+  VLAC_HIP(hipGetLastError());
+  for (int b = 0; b < B; ++b) ctx->filled[b] = 1;
+  return VLAC_OK;
+}
+
+int vlac_decode_action(vlac_ctx* ctx, int B, int L, int n_new, const int32_t* first_token,
+                       void* kv_cache, int32_t* out_tokens, float* out_logits, void* stream) {
+  if (!ctx || !first_token || !kv_cache || !out_tokens) return VLAC_E_NULL;
+  const vlac_model_cfg& m = ctx->cfg;
+  if (B < 1 || B > m.max_batch || L < 1 || n_new < 0) return VLAC_E_RANGE;
+  if ((long)L + n_new > m.max_seq) return VLAC_E_SHAPE;
+  if (!weights_ready(ctx)) return VLAC_E_STATE;
+  for (int b = 0; b < B; ++b)
+    if (!ctx->filled[b]) return VLAC_E_STATE;
+  if (n_new == 0) return VLAC_OK;
+  hipStream_t st = (hipStream_t)stream;
+  launch_decode_plan(ctx, B, L, n_new, st);
+  const int mb = m.max_batch, ms = m.max_seq;
+  const int* rows0 = ctx->dec_rows;
+  const int* n_rows0 = rows0 + (size_t)ms * mb;
+  const int* slot0 = n_rows0 + ms;
+  for (int t = 0; t < n_new; ++t) {
+    const int* rows = rows0 + (size_t)t * mb;
+    const int* n_rows = n_rows0 + t;
+    const int* slot_off = slot0 + (size_t)t * (mb + 1);
+    launch_embed_rows(ctx->embed, t == 0 ? first_token : ctx->tokens, B, m.d_model, m.vocab, ctx->h,
+                      ms, L + t, st);
+    for (int l = 0; l < m.n_layers; ++l)
+      run_layer(ctx, l, B, B, 1, 0, 0, ctx->h, ms, rows, n_rows, slot_off, (bf16_t*)kv_cache,
+                nullptr, st);
+    run_head(ctx, B, rows, n_rows, out_logits ? out_logits + (size_t)t * m.vocab : ctx->logits,
+             out_logits ? (size_t)n_new * m.vocab : (size_t)m.vocab, out_tokens + t, n_new,
+             ctx->tokens, st);
+  }
+  VLAC_HIP(hipGetLastError());
+  return VLAC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,154 @@
+// Internal declarations shared by the kernels and the C-ABI layer of vlac.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "vlac.h"
+
+typedef uint16_t bf16_t;  // raw bf16 bits
+
+// ---------------------------------------------------------------------------
+// Fragment order.  Every bf16 operand of a matrix-core GEMM ([R rows, K cols],
+// weights and activations alike) is stored as tiles of 32 rows x 16 cols.  A
+// tile is 1 KiB: 64 lanes x 8 bf16, lane = (row % 32) + 32 * ((col % 16) / 8),
+// element = col % 8, which is exactly what one v_mfma_f32_32x32x16_bf16 operand
+// wants per lane, so a wave fetches a tile with one coalesced 16-byte load per
+// lane.  Tiles are ordered [row tile][col tile]; KC = padded K / 16.
+// ---------------------------------------------------------------------------
+__host__ __device__ inline size_t frag_off(int row, int col, int KC) {
+  return ((size_t)(row >> 5) * KC + (col >> 4)) * 512 +
+         (size_t)((((row & 31) + (((col >> 3) & 1) << 5)) << 3) + (col & 7));
+}
+
+static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+#ifdef __HIPCC__
+__device__ inline bf16_t f2bf(float x) {  // fp32 -> bf16, round to nearest even
+  uint32_t u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+#endif
+
+enum { VLAC_ERR_BAD_INDEX = 1 };  // bits of the device-side error word
+
+struct LayerW {
+  bf16_t *wqkv, *wo, *wgu, *wdown;  // fragment order
+  float *g_attn, *g_ffn;
+};
+
+struct vlac_ctx {
+  vlac_model_cfg cfg;
+  int device;
+  int last_hip;
+  // derived
+  int q_dim, kv_dim, qkv_dim, group;
+  int kpad_d, kpad_q, kpad_f;  // K padded to 64 for d_model, Hq*hd, d_ffn
+  int max_rows;                // max_batch * max_seq
+  // weights
+  LayerW* layers;  // host array
+  uint8_t* layer_set;
+  bool head_set;
+  bf16_t *w_head, *embed;
+  float* g_final;
+  float *rope_cos, *rope_sin;  // [max_seq, hd/2]
+  // workspace (device)
+  float* h;         // residual stream [max_batch, max_seq, d]
+  bf16_t* xa;       // normed rows / attention output, fragment order
+  bf16_t* xf;       // SwiGLU output, fragment order
+  bf16_t* qbuf;     // rotated queries, fragment order per head
+  float* partial;   // split-K partial sums
+  size_t partial_floats;
+  int* counters;    // split-K arrival counters (self-resetting)
+  int n_counters;
+  int* rows;        // [n_layers + 1][max_rows] (b << 16 | pos); last plane: head rows
+  int* n_rows;      // [n_layers + 1]
+  int* slot_off;    // [n_layers + 1][max_batch + 1]
+  int* rank;        // [max_batch][max_seq] position of a token in its reuse order
+  int* m_layer;     // [max_batch][n_layers]
+  int* n_rows_bl;   // [n_layers][max_batch]
+  float* statp;     // attention-statistic partial sums
+  int stat_tt;      // text tiles per stream the statistic buffer provides for
+  int* stat_counters;
+  float* logits;    // [max_batch, vocab]
+  int* tokens;      // [max_batch] current token of the decode loop
+  int* dec_rows;    // decode row lists
+  uint32_t* terms;  // patch terms [max_batch, 4096, 3]
+  uint8_t* flags;   // selection flags
+  float* relevance; // [max_batch, 4096]
+  int* errword;     // device error bits
+  int* scratch_i;   // small int scratch
+  uint8_t* filled;  // host: stream cache holds a prefill
+  uint8_t* was_reset;
+};
+
+#define VLAC_HIP(call)                         \
+  do {                                         \
+    hipError_t e_ = (call);                    \
+    if (e_ != hipSuccess) {                    \
+      if (ctx) ctx->last_hip = (int)e_;        \
+      return VLAC_E_HIP;                       \
+    }                                          \
+  } while (0)
+
+// ---- launchers implemented in the .hip files (all asynchronous on `st`) ----
+
+// select.hip
+void launch_patch_terms(const uint8_t* prev, const uint8_t* cur, int B, int H, int W, int patch,
+                        uint32_t* terms, hipStream_t st);
+void launch_select(const uint32_t* terms, int B, int L_v, int tau_num, int tau_den, int top_k,
+                   const float* attn_mean, int n_layers, const uint8_t* layer_mask_host, int n_rel,
+                   uint8_t* flags, float* relevance_ws, int32_t* out_idx, int32_t* out_order,
+                   int32_t* out_count, float* out_relevance, int stride, hipStream_t st);
+void launch_layer_ratio(const float* attn_mean, int n_layers, int B, int L_v, float gain_k,
+                        const int32_t* reuse_count, float* out_alpha, int32_t* out_layer_count,
+                        hipStream_t st);
+
+// rows.hip
+void launch_plan(vlac_ctx* c, int B, int L_v, int L_t, const int32_t* reuse_order,
+                 const int32_t* reuse_count, int stride, const int32_t* layer_count, hipStream_t st);
+void launch_decode_plan(vlac_ctx* c, int B, int L, int n_new, hipStream_t st);
+void launch_rmsnorm_rows(const float* src, int seq_stride, const int* rows, const int* n_rows,
+                         int max_rows, const float* gain, float eps, int d, bf16_t* xp, int KC,
+                         hipStream_t st);
+void launch_final_hidden(const float* src, int seq_stride, const int* rows, const int* n_rows,
+                         int max_rows, const float* gain, float eps, int d, float* out, int L,
+                         hipStream_t st);
+void launch_argmax(const float* logits, size_t logits_stride, int B, int vocab, int32_t* out,
+                   int out_stride, int32_t* out2, hipStream_t st);
+void launch_embed_rows(const bf16_t* embed, const int32_t* tokens, int B, int d, int vocab, float* h,
+                       int max_seq, int pos, hipStream_t st);
+void launch_pack(const bf16_t* src, int N, int K, bf16_t* dst, int n_pack, int kpad, int mode,
+                 int p0, int p1, int p2, hipStream_t st);
+void launch_bf16_to_f32(const bf16_t* src, float* dst, int n, hipStream_t st);
+
+// gemm.hip
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
+struct GemmEpi {
+  const int* rows;
+  // EPI_QKV
+  const float *rope_cos, *rope_sin;
+  bf16_t* qbuf;
+  bf16_t* kv;             // cache base of layer 0, stream 0
+  size_t kv_stream_stride, kv_layer_off;
+  int n_q_heads, n_kv_heads, head_dim, max_seq;
+  // EPI_RESID
+  const float* resid_src; int resid_seq_stride;
+  float* h; int d_model;
+  // EPI_SWIGLU
+  bf16_t* xf; int kc_f; int d_ffn;
+  // EPI_LOGITS
+  float* logits; int vocab; size_t logits_stride;  // elements between rows
+};
+int gemm_init();  // one-time kernel attribute setup; returns hipError_t
+void launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, const bf16_t* xp,
+                 const int* n_rows, int rows_cap, const GemmEpi& e, hipStream_t st);
+
+// attn.hip
+void launch_attention(vlac_ctx* c, int layer, int B, int rows_cap_per_stream, int L_v, int L_t,
+                      const int* rows, const int* slot_off, bf16_t* kv, float* out_attn_mean,
+                      hipStream_t st);

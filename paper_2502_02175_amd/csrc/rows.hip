@@ -1,0 +1,345 @@
+// Row bookkeeping and the HBM-bound row kernels of the sparse prefill
+// (Alg. 2 of VLA-Cache; appendix "Token Reuse Mechanism": the list of positions
+// to recompute, recomputed rows keep their original positions).
+//
+//   plan_counts / plan_rows   per layer, the recomputed rows of every stream
+//   rmsnorm_rows              gather a row of the residual stream, RMSNorm, write
+//                             it as a bf16 matrix-core operand (fragment order)
+//   final_hidden              final RMSNorm to fp32 (output)
+//   argmax_rows, embed_rows   greedy token, token embedding lookup (decode)
+//   pack_weights              weights -> fragment order (once per model)
+#include "common.h"
+
+// ---------------------------------------------------------------------------
+// plan_counts: grid (B).  rank[b, v] = position of token v in stream b's reuse
+// order (INT_MAX if it is not reusable); m_layer[b, l] = how many entries of the
+// reuse order layer l reuses (clamped, non-decreasing over l);
+// n_rows_bl[l, b] = rows stream b recomputes at layer l.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void plan_counts_kernel(
+    int L_v, int L_t, int n_layers, int max_seq, const int32_t* __restrict__ reuse_order,
+    const int32_t* __restrict__ reuse_count, int stride, const int32_t* __restrict__ layer_count,
+    int* __restrict__ rank, int* __restrict__ m_layer, int* __restrict__ n_rows_bl, int B,
+    int* __restrict__ errword) {
+  __shared__ int red[4];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  int* rk = rank + (size_t)b * max_seq;
+  for (int v = tid; v < L_v; v += 256) rk[v] = 0x7fffffff;
+  __syncthreads();
+  int cnt = 0;
+  if (reuse_order && reuse_count) {
+    cnt = reuse_count[b];
+    if (cnt < 0 || cnt > stride) {
+      if (tid == 0) atomicOr(errword, VLAC_ERR_BAD_INDEX);
+      cnt = cnt < 0 ? 0 : stride;
+    }
+    for (int i = tid; i < cnt; i += 256) {
+      const int v = reuse_order[(size_t)b * stride + i];
+      if (v >= 0 && v < L_v) {
+        const int old = atomicMin(&rk[v], i);
+        if (old != 0x7fffffff) atomicOr(errword, VLAC_ERR_BAD_INDEX);  // repeated entry
+      } else {
+        atomicOr(errword, VLAC_ERR_BAD_INDEX);
+      }
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int best = 0;
+    for (int l = 0; l < n_layers; ++l) {
+      int m = layer_count ? layer_count[(size_t)b * n_layers + l] : cnt;
+      m = m < 0 ? 0 : (m > cnt ? cnt : m);
+      best = m > best ? m : best;
+      m_layer[(size_t)b * n_layers + l] = best;
+    }
+  }
+  __syncthreads();
+  for (int l = 0; l < n_layers; ++l) {
+    const int m = m_layer[(size_t)b * n_layers + l];
+    int n = 0;
+    for (int v = tid; v < L_v; v += 256) n += rk[v] < m;
+    for (int o = 32; o > 0; o >>= 1) n += __shfl_down(n, o);
+    __syncthreads();
+    if ((tid & 63) == 0) red[tid >> 6] = n;
+    __syncthreads();
+    if (tid == 0) n_rows_bl[(size_t)l * B + b] = L_v + L_t - (red[0] + red[1] + red[2] + red[3]);
+  }
+}
+
+// plan_rows: grid (n_layers + 1, B).  Plane l < n_layers: rows of layer l, streams
+// packed one after the other, positions ascending.  Plane n_layers: one row per
+// stream, its last position (input of the output head).
+__global__ __launch_bounds__(256) void plan_rows_kernel(
+    int L_v, int L_t, int n_layers, int max_seq, int max_rows, int max_batch,
+    const int* __restrict__ rank, const int* __restrict__ m_layer,
+    const int* __restrict__ n_rows_bl, int B, int* __restrict__ rows, int* __restrict__ n_rows,
+    int* __restrict__ slot_off) {
+  __shared__ int wsum[4];
+  __shared__ int base_s;
+  const int l = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int L = L_v + L_t;
+  if (l == n_layers) {
+    if (tid == 0) {
+      rows[(size_t)l * max_rows + b] = (b << 16) | (L - 1);
+      slot_off[(size_t)l * (max_batch + 1) + b] = b;
+      if (b == B - 1) {
+        slot_off[(size_t)l * (max_batch + 1) + B] = B;
+        n_rows[l] = B;
+      }
+    }
+    return;
+  }
+  int off = 0;
+  for (int k = 0; k < b; ++k) off += n_rows_bl[(size_t)l * B + k];
+  if (tid == 0) {
+    slot_off[(size_t)l * (max_batch + 1) + b] = off;
+    if (b == B - 1) {
+      const int tot = off + n_rows_bl[(size_t)l * B + b];
+      slot_off[(size_t)l * (max_batch + 1) + B] = tot;
+      n_rows[l] = tot;
+    }
+    base_s = off;
+  }
+  __syncthreads();
+  const int m = m_layer[(size_t)b * n_layers + l];
+  const int* rk = rank + (size_t)b * max_seq;
+  for (int c0 = 0; c0 < L; c0 += 256) {
+    const int p = c0 + tid;
+    const int keep = p < L && !(p < L_v && rk[p] < m);
+    const unsigned long long bal = __ballot(keep);
+    const int inwave = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wsum[w] = __popcll(bal);
+    __syncthreads();
+    int o = base_s;
+    for (int k = 0; k < w; ++k) o += wsum[k];
+    if (keep) rows[(size_t)l * max_rows + o + inwave] = (b << 16) | p;
+    __syncthreads();
+    if (tid == 0) base_s += wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    __syncthreads();
+  }
+}
+
+void launch_plan(vlac_ctx* c, int B, int L_v, int L_t, const int32_t* reuse_order,
+                 const int32_t* reuse_count, int stride, const int32_t* layer_count,
+                 hipStream_t st) {
+  const int nl = c->cfg.n_layers;
+  hipLaunchKernelGGL(plan_counts_kernel, dim3(B), dim3(256), 0, st, L_v, L_t, nl, c->cfg.max_seq,
+                     reuse_order, reuse_count, stride, layer_count, c->rank, c->m_layer,
+                     c->n_rows_bl, B, c->errword);
+  hipLaunchKernelGGL(plan_rows_kernel, dim3(nl + 1, B), dim3(256), 0, st, L_v, L_t, nl,
+                     c->cfg.max_seq, c->max_rows, c->cfg.max_batch, c->rank, c->m_layer,
+                     c->n_rows_bl, B, c->rows, c->n_rows, c->slot_off);
+}
+
+// Decode row lists: plane t (0 <= t < n_new) holds row (b, L + t) for every stream.
+__global__ void decode_plan_kernel(int B, int L, int n_new, int max_batch, int* __restrict__ rows,
+                                   int* __restrict__ n_rows, int* __restrict__ slot_off) {
+  const int t = blockIdx.x;
+  for (int b = threadIdx.x; b <= B; b += blockDim.x) {
+    if (b < B) rows[(size_t)t * max_batch + b] = (b << 16) | (L + t);
+    slot_off[(size_t)t * (max_batch + 1) + b] = b;
+  }
+  if (threadIdx.x == 0) n_rows[t] = B;
+}
+
+void launch_decode_plan(vlac_ctx* c, int B, int L, int n_new, hipStream_t st) {
+  // dec_rows layout: [n_new][max_batch] rows, then [n_new] counts, then [n_new][max_batch+1] offsets
+  const int mb = c->cfg.max_batch, ms = c->cfg.max_seq;
+  int* rows = c->dec_rows;
+  int* n_rows = rows + (size_t)ms * mb;
+  int* slot_off = n_rows + ms;
+  hipLaunchKernelGGL(decode_plan_kernel, dim3(n_new), dim3(64), 0, st, B, L, n_new, mb, rows, n_rows,
+                     slot_off);
+}
+
+// ---------------------------------------------------------------------------
+// RMSNorm of the recomputed rows.  One wave per row: x * rsqrt(mean(x^2) + eps) * g,
+// statistics in fp32, output bf16 in fragment order (slot = row of the operand).
+// ---------------------------------------------------------------------------
+__device__ inline float wave_sum(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+__global__ __launch_bounds__(256) void rmsnorm_rows_kernel(
+    const float* __restrict__ src, int seq_stride, const int* __restrict__ rows,
+    const int* __restrict__ n_rows, const float* __restrict__ gain, float eps, int d,
+    bf16_t* __restrict__ xp, int KC) {
+  const int slot = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (slot >= *n_rows) return;
+  const int id = rows[slot];
+  const float* x = src + ((size_t)(id >> 16) * seq_stride + (id & 0xffff)) * d;
+  float ss = 0.f;
+  for (int k = lane * 4; k < d; k += 256) {
+    const float4 v = *(const float4*)(x + k);
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = wave_sum(ss);
+  const float r = rsqrtf(ss / (float)d + eps);
+  for (int k = lane * 8; k < d; k += 512) {
+    const float4 a = *(const float4*)(x + k), b = *(const float4*)(x + k + 4);
+    const float4 ga = *(const float4*)(gain + k), gb = *(const float4*)(gain + k + 4);
+    uint4 o;
+    o.x = f2bf(a.x * r * ga.x) | ((uint32_t)f2bf(a.y * r * ga.y) << 16);
+    o.y = f2bf(a.z * r * ga.z) | ((uint32_t)f2bf(a.w * r * ga.w) << 16);
+    o.z = f2bf(b.x * r * gb.x) | ((uint32_t)f2bf(b.y * r * gb.y) << 16);
+    o.w = f2bf(b.z * r * gb.z) | ((uint32_t)f2bf(b.w * r * gb.w) << 16);
+    *(uint4*)(xp + frag_off(slot, k, KC)) = o;
+  }
+}
+
+void launch_rmsnorm_rows(const float* src, int seq_stride, const int* rows, const int* n_rows,
+                         int max_rows, const float* gain, float eps, int d, bf16_t* xp, int KC,
+                         hipStream_t st) {
+  hipLaunchKernelGGL(rmsnorm_rows_kernel, dim3((max_rows + 3) / 4), dim3(256), 0, st, src,
+                     seq_stride, rows, n_rows, gain, eps, d, xp, KC);
+}
+
+// Final RMSNorm of every row alive at the last layer, fp32 out [B, L, d].
+__global__ __launch_bounds__(256) void final_hidden_kernel(
+    const float* __restrict__ src, int seq_stride, const int* __restrict__ rows,
+    const int* __restrict__ n_rows, const float* __restrict__ gain, float eps, int d,
+    float* __restrict__ out, int L) {
+  const int slot = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (slot >= *n_rows) return;
+  const int id = rows[slot];
+  const float* x = src + ((size_t)(id >> 16) * seq_stride + (id & 0xffff)) * d;
+  float* y = out + ((size_t)(id >> 16) * L + (id & 0xffff)) * d;
+  float ss = 0.f;
+  for (int k = lane * 4; k < d; k += 256) {
+    const float4 v = *(const float4*)(x + k);
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = wave_sum(ss);
+  const float r = rsqrtf(ss / (float)d + eps);
+  for (int k = lane * 4; k < d; k += 256) {
+    const float4 v = *(const float4*)(x + k), g = *(const float4*)(gain + k);
+    *(float4*)(y + k) = make_float4(v.x * r * g.x, v.y * r * g.y, v.z * r * g.z, v.w * r * g.w);
+  }
+}
+
+void launch_final_hidden(const float* src, int seq_stride, const int* rows, const int* n_rows,
+                         int max_rows, const float* gain, float eps, int d, float* out, int L,
+                         hipStream_t st) {
+  hipLaunchKernelGGL(final_hidden_kernel, dim3((max_rows + 3) / 4), dim3(256), 0, st, src,
+                     seq_stride, rows, n_rows, gain, eps, d, out, L);
+}
+
+// ---------------------------------------------------------------------------
+// Greedy token: argmax over the vocabulary, ties -> lower id.  grid (B).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits,
+                                                     size_t logits_stride, int vocab,
+                                                     int32_t* __restrict__ out, int out_stride,
+                                                     int32_t* __restrict__ out2) {
+  __shared__ float bv[4];
+  __shared__ int bi[4];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const float* x = logits + (size_t)b * logits_stride;
+  float best = -INFINITY;
+  int idx = 0x7fffffff;
+  for (int i = tid; i < vocab; i += 256) {
+    const float v = x[i];
+    if (v > best || (v == best && i < idx)) { best = v; idx = i; }
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    const float v = __shfl_xor(best, o);
+    const int i = __shfl_xor(idx, o);
+    if (v > best || (v == best && i < idx)) { best = v; idx = i; }
+  }
+  if ((tid & 63) == 0) { bv[tid >> 6] = best; bi[tid >> 6] = idx; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int k = 1; k < 4; ++k)
+      if (bv[k] > best || (bv[k] == best && bi[k] < idx)) { best = bv[k]; idx = bi[k]; }
+    if (idx == 0x7fffffff) idx = 0;  // every logit NaN: still a valid id
+    out[(size_t)b * out_stride] = idx;
+    if (out2) out2[b] = idx;
+  }
+}
+
+void launch_argmax(const float* logits, size_t logits_stride, int B, int vocab, int32_t* out,
+                   int out_stride, int32_t* out2, hipStream_t st) {
+  hipLaunchKernelGGL(argmax_kernel, dim3(B), dim3(256), 0, st, logits, logits_stride, vocab, out,
+                     out_stride, out2);
+}
+
+// Token embedding rows into the residual stream at position `pos`.  grid (B).
+__global__ __launch_bounds__(256) void embed_rows_kernel(const bf16_t* __restrict__ embed,
+                                                         const int32_t* __restrict__ tokens, int d,
+                                                         int vocab, float* __restrict__ h,
+                                                         int max_seq, int pos) {
+  const int b = blockIdx.x;
+  int tok = tokens[b];
+  tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
+  const bf16_t* e = embed + (size_t)tok * d;
+  float* y = h + ((size_t)b * max_seq + pos) * d;
+  for (int k = threadIdx.x; k < d; k += 256) y[k] = __uint_as_float((uint32_t)e[k] << 16);
+}
+
+void launch_embed_rows(const bf16_t* embed, const int32_t* tokens, int B, int d, int vocab, float* h,
+                       int max_seq, int pos, hipStream_t st) {
+  hipLaunchKernelGGL(embed_rows_kernel, dim3(B), dim3(256), 0, st, embed, tokens, d, vocab, h,
+                     max_seq, pos);
+}
+
+// ---------------------------------------------------------------------------
+// Weights [N, K] row-major -> fragment order, with a row permutation:
+//   mode 0  identity
+//   mode 1  QKV (p0 = Hq*hd, p1 = Hkv*hd, p2 = hd): inside every 32-row block of a
+//           query or key head the two rotary partners (f, f + hd/2) of 16
+//           features sit 16 rows apart, so one lane of the GEMM epilogue holds
+//           both; value heads keep their order
+//   mode 2  gate/up (p0 = F): every 32-row block holds 16 gate rows followed by
+//           the 16 matching up rows
+// Rows >= n_pack sources and columns >= K are zero.
+// ---------------------------------------------------------------------------
+__device__ inline int pack_src_row(int pr, int mode, int p0, int p1, int p2) {
+  if (mode == 1) {
+    if (pr >= p0 + p1) return pr;
+    const int hd = p2, within = pr % hd, sb = within >> 5, i = within & 31;
+    const int f = (i < 16) ? 16 * sb + i : hd / 2 + 16 * sb + (i - 16);
+    return pr - within + f;
+  }
+  if (mode == 2) {
+    const int blk = pr >> 5, i = pr & 31;
+    return (i < 16) ? 16 * blk + i : p0 + 16 * blk + (i - 16);
+  }
+  return pr;
+}
+
+__global__ __launch_bounds__(256) void pack_weights_kernel(const bf16_t* __restrict__ src, int N,
+                                                           int K, bf16_t* __restrict__ dst,
+                                                           int n_pack, int kpad, int mode, int p0,
+                                                           int p1, int p2) {
+  const int KC = kpad / 16;
+  const size_t n_chunks = (size_t)(n_pack / 32) * KC * 64;  // 16-byte chunks
+  for (size_t c = (size_t)blockIdx.x * 256 + threadIdx.x; c < n_chunks;
+       c += (size_t)gridDim.x * 256) {
+    const int lane = (int)(c & 63);
+    const size_t tile = c >> 6;
+    const int kc = (int)(tile % KC), rt = (int)(tile / KC);
+    const int pr = rt * 32 + (lane & 31), col = kc * 16 + 8 * (lane >> 5);
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (col < K) {
+      const int sr = pack_src_row(pr, mode, p0, p1, p2);
+      if (sr < N) v = *(const uint4*)(src + (size_t)sr * K + col);
+    }
+    *(uint4*)(dst + c * 8) = v;
+  }
+}
+
+void launch_pack(const bf16_t* src, int N, int K, bf16_t* dst, int n_pack, int kpad, int mode,
+                 int p0, int p1, int p2, hipStream_t st) {
+  hipLaunchKernelGGL(pack_weights_kernel, dim3(2048), dim3(256), 0, st, src, N, K, dst, n_pack,
+                     kpad, mode, p0, p1, p2);
+}
+
+__global__ void bf16_to_f32_kernel(const bf16_t* __restrict__ src, float* __restrict__ dst, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = __uint_as_float((uint32_t)src[i] << 16);
+}
+
+void launch_bf16_to_f32(const bf16_t* src, float* dst, int n, hipStream_t st) {
+  hipLaunchKernelGGL(bf16_to_f32_kernel, dim3((n + 255) / 256), dim3(256), 0, st, src, dst, n);
+}

@@ -1,0 +1,299 @@
+// Token selection (Alg. 1 of VLA-Cache) and the layer-adaptive ratio (Sec. 3.4).
+//
+//   patch_terms_kernel   Eq. (sim): per patch the exact integers dot, |P_t|^2, |P_{t-1}|^2
+//   select_rank_kernel   threshold (Sim >= tau, cross-multiplied in 128-bit integers),
+//                        Top-k by exact rational comparison (Eq. topk), task-relevance
+//                        quantile filter (Eq. ptask, Eq. pfinal)
+//   select_compact_kernel  ascending index list and reuse order
+//   layer_ratio_kernel   entropy ratio and Eq. (reuse_ratio), in fp64
+//
+// All of this is HBM/latency-bound integer work: 2*H*W*3 bytes of pixels per
+// stream are read exactly once, with 16-byte loads over the contiguous run of
+// image rows that one row of patches covers.
+#include "common.h"
+
+typedef unsigned __int128 u128;
+
+// ---------------------------------------------------------------------------
+// Eq. (sim) terms.  One workgroup per (patch row, stream).
+// ---------------------------------------------------------------------------
+template <int VEC>
+__global__ __launch_bounds__(256) void patch_terms_kernel(const uint8_t* __restrict__ prev,
+                                                          const uint8_t* __restrict__ cur, int H,
+                                                          int W, int patch,
+                                                          uint32_t* __restrict__ terms) {
+  extern __shared__ uint32_t acc[];  // [gw][3]
+  const int gw = W / patch, gh = H / patch;
+  const int b = blockIdx.y, pr = blockIdx.x, tid = threadIdx.x;
+  const size_t base = ((size_t)b * H + (size_t)pr * patch) * W * 3;
+  const int rowbytes = W * 3, pbytes = patch * 3, nbytes = patch * rowbytes;
+  for (int i = tid; i < gw * 3; i += 256) acc[i] = 0;
+  __syncthreads();
+  for (int o = tid * VEC; o < nbytes; o += 256 * VEC) {
+    uint32_t av[4] = {0, 0, 0, 0}, bv[4] = {0, 0, 0, 0};
+    if constexpr (VEC == 16) {
+      const uint4 a4 = *(const uint4*)(cur + base + o);
+      const uint4 b4 = *(const uint4*)(prev + base + o);
+      av[0] = a4.x; av[1] = a4.y; av[2] = a4.z; av[3] = a4.w;
+      bv[0] = b4.x; bv[1] = b4.y; bv[2] = b4.z; bv[3] = b4.w;
+    } else {
+      av[0] = cur[base + o];
+      bv[0] = prev[base + o];
+    }
+    const int c = o % rowbytes;
+    int j = c / pbytes, within = c % pbytes;
+    uint32_t d = 0, na = 0, nb = 0;
+    auto flush = [&]() {
+      if (d | na | nb) {
+        atomicAdd(&acc[j * 3 + 0], d);
+        atomicAdd(&acc[j * 3 + 1], na);
+        atomicAdd(&acc[j * 3 + 2], nb);
+      }
+      d = na = nb = 0;
+    };
+    auto advance = [&](int n) {
+      within += n;
+      if (within == pbytes) {
+        flush();
+        within = 0;
+        if (++j == gw) j = 0;
+      }
+    };
+    if constexpr (VEC == 16) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (within + 4 <= pbytes) {  // the whole dword lies in one patch
+          d = __builtin_amdgcn_udot4(av[k], bv[k], d, false);
+          na = __builtin_amdgcn_udot4(av[k], av[k], na, false);
+          nb = __builtin_amdgcn_udot4(bv[k], bv[k], nb, false);
+          advance(4);
+        } else {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const uint32_t x = (av[k] >> (8 * q)) & 255u, y = (bv[k] >> (8 * q)) & 255u;
+            d += x * y; na += x * x; nb += y * y;
+            advance(1);
+          }
+        }
+      }
+    } else {
+      d = av[0] * bv[0]; na = av[0] * av[0]; nb = bv[0] * bv[0];
+      advance(1);
+    }
+    flush();
+  }
+  __syncthreads();
+  const int Lv = gw * gh;
+  for (int i = tid; i < gw * 3; i += 256)
+    terms[((size_t)b * Lv + (size_t)pr * gw) * 3 + i] = acc[i];
+}
+
+void launch_patch_terms(const uint8_t* prev, const uint8_t* cur, int B, int H, int W, int patch,
+                        uint32_t* terms, hipStream_t st) {
+  const int gw = W / patch, gh = H / patch;
+  const size_t shm = (size_t)gw * 3 * sizeof(uint32_t);
+  const bool vec = ((size_t)patch * W * 3) % 16 == 0 && ((size_t)H * W * 3) % 16 == 0 &&
+                   ((uintptr_t)prev % 16 == 0) && ((uintptr_t)cur % 16 == 0);
+  dim3 grid(gh, B);
+  if (vec)
+    hipLaunchKernelGGL(patch_terms_kernel<16>, grid, dim3(256), shm, st, prev, cur, H, W, patch, terms);
+  else
+    hipLaunchKernelGGL(patch_terms_kernel<1>, grid, dim3(256), shm, st, prev, cur, H, W, patch, terms);
+}
+
+// ---------------------------------------------------------------------------
+// Threshold, Top-k, relevance filter.
+// ---------------------------------------------------------------------------
+struct Frac { uint64_t num, den; };  // Sim^2 as an exact fraction
+
+__device__ inline Frac sim_fraction(uint32_t dot, uint32_t na, uint32_t nb) {
+  // two all-zero patches are identical, exactly one all-zero patch is dissimilar
+  if (na == 0 && nb == 0) return {1, 1};
+  if (na == 0 || nb == 0) return {0, 1};
+  return {(uint64_t)dot * dot, (uint64_t)na * nb};
+}
+
+#define SEL_MAX_LV 4096
+struct LayerMask { uint32_t w[16]; };  // bit l set = layer l is averaged over (<= 512 layers)
+
+// grid (ceil(L_v / 256), B).  flags[b, i] = 1 iff patch i is in P_final.
+__global__ __launch_bounds__(256) void select_rank_kernel(
+    const uint32_t* __restrict__ terms, int L_v, uint64_t tn2, uint64_t td2, int top_k,
+    const float* __restrict__ attn_mean, int n_layers, int B, LayerMask layer_mask, int n_rel, uint8_t* __restrict__ flags, float* __restrict__ relevance) {
+  __shared__ double approx[SEL_MAX_LV];
+  __shared__ float score[SEL_MAX_LV];
+  __shared__ uint8_t pass[SEL_MAX_LV];
+  const int b = blockIdx.y, tid = threadIdx.x;
+  const uint32_t* t = terms + (size_t)b * L_v * 3;
+  for (int j = tid; j < L_v; j += 256) {
+    const Frac f = sim_fraction(t[j * 3], t[j * 3 + 1], t[j * 3 + 2]);
+    pass[j] = (u128)f.num * td2 >= (u128)tn2 * f.den;
+    approx[j] = (double)f.num / (double)f.den;
+    float s = 0.f;
+    if (attn_mean) {
+      int n = 0;
+      for (int l = 0; l < n_layers; ++l)
+        if ((layer_mask.w[l >> 5] >> (l & 31)) & 1u) {
+          s += attn_mean[((size_t)l * B + b) * L_v + j];
+          ++n;
+        }
+      s = s / (float)(n > 0 ? n : 1);
+    }
+    score[j] = s;
+  }
+  __syncthreads();
+  const int i = blockIdx.x * 256 + tid;
+  if (i >= L_v) return;
+  bool keep = pass[i] && top_k > 0;
+  if (keep) {
+    // rank among the passers: higher similarity first, ties -> lower index
+    const double ai = approx[i];
+    const Frac fi = sim_fraction(t[i * 3], t[i * 3 + 1], t[i * 3 + 2]);
+    int rank = 0;
+    for (int j = 0; j < L_v; ++j) {
+      if (!pass[j] || j == i) continue;
+      const double dlt = approx[j] - ai;
+      bool beats;
+      if (dlt > 1e-12) beats = true;
+      else if (dlt < -1e-12) beats = false;
+      else {  // too close for fp64: exact cross-multiplication
+        const Frac fj = sim_fraction(t[j * 3], t[j * 3 + 1], t[j * 3 + 2]);
+        const u128 lhs = (u128)fj.num * fi.den, rhs = (u128)fi.num * fj.den;
+        beats = lhs > rhs || (lhs == rhs && j < i);
+      }
+      rank += beats;
+    }
+    keep = rank < top_k;
+  }
+  if (attn_mean) {
+    const float si = score[i];
+    if (keep && n_rel > 0) {
+      int rr = 0;  // rank by score descending, ties -> lower index
+      for (int j = 0; j < L_v; ++j) rr += (score[j] > si) || (score[j] == si && j < i);
+      keep = rr >= n_rel;
+    }
+    relevance[(size_t)b * L_v + i] = si;
+  } else {
+    relevance[(size_t)b * L_v + i] = 0.f;
+  }
+  flags[(size_t)b * L_v + i] = keep;
+}
+
+// grid (B).  Ascending list, count, and the list ordered by (score asc, index asc).
+__global__ __launch_bounds__(256) void select_compact_kernel(
+    const uint8_t* __restrict__ flags, const float* __restrict__ relevance, int L_v,
+    int32_t* __restrict__ out_idx, int32_t* __restrict__ out_order, int32_t* __restrict__ out_count,
+    float* __restrict__ out_relevance, int stride) {
+  __shared__ float score[SEL_MAX_LV];
+  __shared__ uint8_t fl[SEL_MAX_LV];
+  __shared__ int wsum[4];
+  __shared__ int base_s;
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  for (int j = tid; j < L_v; j += 256) {
+    fl[j] = flags[(size_t)b * L_v + j];
+    score[j] = relevance[(size_t)b * L_v + j];
+    if (out_relevance) out_relevance[(size_t)b * L_v + j] = score[j];
+  }
+  if (tid == 0) base_s = 0;
+  __syncthreads();
+  for (int c0 = 0; c0 < L_v; c0 += 256) {
+    const int i = c0 + tid;
+    const int f = (i < L_v) ? fl[i] : 0;
+    const unsigned long long bal = __ballot(f);
+    const int inwave = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wsum[w] = __popcll(bal);
+    __syncthreads();
+    int off = base_s;
+    for (int k = 0; k < w; ++k) off += wsum[k];
+    if (f) {
+      const int k = off + inwave;
+      if (k < stride) out_idx[(size_t)b * stride + k] = i;
+      int ord = 0;
+      const float si = score[i];
+      for (int j = 0; j < L_v; ++j)
+        ord += fl[j] && ((score[j] < si) || (score[j] == si && j < i));
+      if (ord < stride) out_order[(size_t)b * stride + ord] = i;
+    }
+    __syncthreads();
+    if (tid == 0) base_s += wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    __syncthreads();
+  }
+  if (tid == 0) out_count[b] = base_s;
+}
+
+void launch_select(const uint32_t* terms, int B, int L_v, int tau_num, int tau_den, int top_k,
+                   const float* attn_mean, int n_layers, const uint8_t* layer_mask_host, int n_rel,
+                   uint8_t* flags, float* relevance_ws, int32_t* out_idx, int32_t* out_order,
+                   int32_t* out_count, float* out_relevance, int stride, hipStream_t st) {
+  const uint64_t tn2 = (uint64_t)tau_num * (uint64_t)tau_num;
+  const uint64_t td2 = (uint64_t)tau_den * (uint64_t)tau_den;
+  LayerMask lm;
+  for (int i = 0; i < 16; ++i) lm.w[i] = 0;
+  for (int l = 0; l < n_layers && l < 512; ++l)
+    if (!layer_mask_host || layer_mask_host[l]) lm.w[l >> 5] |= 1u << (l & 31);
+  hipLaunchKernelGGL(select_rank_kernel, dim3((L_v + 255) / 256, B), dim3(256), 0, st, terms, L_v,
+                     tn2, td2, top_k, attn_mean, n_layers, B, lm, n_rel, flags,
+                     relevance_ws);
+  hipLaunchKernelGGL(select_compact_kernel, dim3(B), dim3(256), 0, st, flags, relevance_ws, L_v,
+                     out_idx, out_order, out_count, out_relevance, stride);
+}
+
+// ---------------------------------------------------------------------------
+// Sec. 3.4.  grid (B), fp64 throughout; sums are fixed-shape trees, so the
+// result does not depend on scheduling.
+// ---------------------------------------------------------------------------
+__device__ inline double block_sum(double v, double* red) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) red[w] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+#define RATIO_MAX_LAYERS 512
+
+__global__ __launch_bounds__(256) void layer_ratio_kernel(
+    const float* __restrict__ attn_mean, int n_layers, int B, int L_v, float gain_k,
+    const int32_t* __restrict__ reuse_count, float* __restrict__ out_alpha,
+    int32_t* __restrict__ out_layer_count) {
+  __shared__ double red[4];
+  __shared__ double ent[RATIO_MAX_LAYERS];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  for (int l = 0; l < n_layers; ++l) {
+    const float* a = attn_mean + ((size_t)l * B + b) * L_v;
+    double s = 0;
+    for (int v = tid; v < L_v; v += 256) s += (double)a[v];
+    const double tot = block_sum(s, red);
+    double e = 0;
+    if (tot > 0)
+      for (int v = tid; v < L_v; v += 256) {
+        const double p = (double)a[v] / tot;
+        if (p > 0) e -= p * log(p);
+      }
+    e = block_sum(e, red);
+    if (tid == 0) ent[l] = tot > 0 ? e : 0.0;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    double cum = 0, best = 0;
+    const int cnt = reuse_count ? reuse_count[b] : 0;
+    for (int l = 0; l < n_layers; ++l) {
+      if (l > 0 && ent[l - 1] > 0) cum += (ent[l - 1] - ent[l]) / ent[l - 1];
+      double al = (double)gain_k * cum;
+      al = al < 0 ? 0 : (al > 1 ? 1 : al);
+      best = al > best ? al : best;
+      const float af = (float)best;
+      out_alpha[(size_t)b * n_layers + l] = af;
+      if (out_layer_count)
+        out_layer_count[(size_t)b * n_layers + l] = (int)floorf(af * (float)(cnt > 0 ? cnt : 0));
+    }
+  }
+}
+
+void launch_layer_ratio(const float* attn_mean, int n_layers, int B, int L_v, float gain_k,
+                        const int32_t* reuse_count, float* out_alpha, int32_t* out_layer_count,
+                        hipStream_t st) {
+  hipLaunchKernelGGL(layer_ratio_kernel, dim3(B), dim3(256), 0, st, attn_mean, n_layers, B, L_v,
+                     gain_k, reuse_count, out_alpha, out_layer_count);
+}
