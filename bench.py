@@ -1,0 +1,265 @@
+#!/usr/bin/env python3
+"""Benchmark of the VLA-Cache control step on one MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic frame pair:
+  vlac_select_static -> vlac_layer_ratio -> vlac_sparse_prefill -> vlac_decode_action
+with every input already resident in HBM.  Prints ONE JSON line.
+
+Workload (default "c2"): OpenVLA-7B decoder shape (32 layers, d 4096, 32 heads x
+128, SwiGLU 11008, vocab 32000), one stream, 224x224 frames = 256 visual tokens +
+32 text tokens, 77 of 256 patches re-drawn and 179 near-static, top-k 180, then
+6 further greedy action tokens (7 in all).  Random-init weights, synthetic
+seeded frames.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+N_ACTION = 7
+
+KIND_NAMES = {0: "qkv_rope_scatter", 1: "proj_residual", 2: "gate_up_swiglu", 3: "head_logits"}
+CLASS_NAMES = {0: "rows<=32 (decode, head)", 1: "rows>32 (prefill)"}
+
+
+def gemm_bytes(cfg, epi, rows):
+    """Algorithmic HBM bytes of one GEMM launch: the bf16 weights once, plus the
+    row operands in and the results out (both small)."""
+    d, F = cfg.d_model, cfg.d_ffn
+    qkv = cfg.q_dim + 2 * cfg.kv_dim
+    if epi == 0:
+        return 2 * qkv * d + rows * d * 2 + rows * qkv * 2
+    if epi == 2:
+        return 2 * 2 * F * d + rows * d * 2 + rows * F * 2
+    if epi == 3:
+        return 2 * cfg.vocab * d + rows * d * 2 + rows * cfg.vocab * 4
+    # epi 1 is used for two shapes (attention output and FFN down): their mean
+    return (2 * d * cfg.q_dim + rows * cfg.q_dim * 2 + 2 * d * F + rows * F * 2) // 2 + rows * d * 8
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2", choices=["c2"])
+    ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers than the model has")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=3)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path is single-GPU; streams would "
+              "shard data-parallel with no exchange); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth
+    import paper_2502_02175_amd as V
+    from harness import GpuModel
+
+    if not os.path.exists(V.lib_path()):
+        from paper_2502_02175_amd import build as _b
+        _b.build()
+    V.lib()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    cfg = synth.CONFIGS["7b"]
+    if args.layers:
+        cfg = cfg.with_layers(args.layers)
+    seed, H, patch, n_vis, n_txt, top_k, n_redraw = 0, 224, 14, 256, 32, 180, 77
+    L = n_vis + n_txt
+    n_new = N_ACTION - 1
+    gm = GpuModel(cfg, seed, max_batch=1, max_seq=320, gain_jitter=0.0, gen_device=dev)
+    ctx, kv = gm.ctx, gm.kv
+
+    prev, cur, redrawn = synth.frame_pair(H, H, patch, n_redraw, seed)
+    wp = synth.projection_matrix(cfg.d_model, patch, seed + 1)
+    txt = synth.round_bf16(synth.text_embeddings(n_txt, cfg.d_model, seed + 2))
+    e_prev = np.concatenate([synth.round_bf16(synth.visual_embeddings(prev, patch, wp)), txt])
+    e_cur = np.concatenate([synth.round_bf16(synth.visual_embeddings(cur, patch, wp)), txt])
+
+    t = lambda a, dt=None: torch.tensor(a, device=dev, dtype=dt)
+    d_prev, d_cur = t(prev[None]), t(cur[None])
+    d_eprev, d_ecur = t(e_prev[None]), t(e_cur[None])
+    nl = cfg.n_layers
+    attn_a = torch.zeros((nl, 1, n_vis), device=dev)
+    attn_b = torch.zeros((nl, 1, n_vis), device=dev)
+    idx = torch.zeros((1, top_k), dtype=torch.int32, device=dev)
+    order = torch.zeros((1, top_k), dtype=torch.int32, device=dev)
+    cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+    alpha = torch.zeros((1, nl), device=dev)
+    lcount = torch.zeros((1, nl), dtype=torch.int32, device=dev)
+    logits = torch.zeros((1, cfg.vocab), device=dev)
+    tok = torch.zeros(1, dtype=torch.int32, device=dev)
+    toks = torch.zeros((1, n_new), dtype=torch.int32, device=dev)
+
+    def full_prefill(emb, attn_out):
+        V.vlac_sparse_prefill(ctx, emb, 1, n_vis, n_txt, None, None, 1, None, kv, attn_out, None,
+                              logits, tok)
+
+    def sparse_step(events=None):
+        if events:
+            events[0].record()
+        # Alg. 1 on the previous step's statistics; tau_task = 1: no token is task-relevant,
+        # so all 179 static patches are reused (70% static, as the workload prescribes)
+        V.vlac_select_static(ctx, d_prev, d_cur, 1, H, H, patch, 249, 250, top_k, attn_a, None, 1.0,
+                             idx, order, cnt, None, top_k)
+        V.vlac_layer_ratio(ctx, attn_a, 1, n_vis, 1.0, cnt, alpha, lcount)
+        if events:
+            events[1].record()
+        # every layer reuses all of P_final (layer_count NULL); alpha is computed and reported only
+        V.vlac_sparse_prefill(ctx, d_ecur, 1, n_vis, n_txt, order, cnt, top_k, None, kv, attn_b,
+                              None, logits, tok)
+        if events:
+            events[2].record()
+        V.vlac_decode_action(ctx, 1, L, n_new, tok, kv, toks, None)
+        if events:
+            events[3].record()
+
+    def full_step(events=None):
+        if events:
+            events[0].record()
+            events[1].record()
+        full_prefill(d_ecur, attn_b)
+        if events:
+            events[2].record()
+        V.vlac_decode_action(ctx, 1, L, n_new, tok, kv, toks, None)
+        if events:
+            events[3].record()
+
+    def timed(step, steps, warmup):
+        for _ in range(warmup):
+            step()
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(evs[i])
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        ph = np.array([[e[k].elapsed_time(e[k + 1]) for k in range(3)] for e in evs])
+        return wall, ph.mean(axis=0)
+
+    # frame t-1: full prefill fills the cache and yields the statistics Alg. 1 needs
+    full_prefill(d_eprev, attn_a)
+    torch.cuda.synchronize()
+
+    ms_step, (ms_sel, ms_prefill, ms_decode) = timed(sparse_step, args.steps, args.warmup)
+    V.vlac_check(ctx)
+    n_reused = int(cnt.cpu()[0])
+    n_rows = L - n_reused
+    ms_full_step, (_, ms_full_prefill, ms_full_decode) = timed(full_step, max(args.steps // 2, 5),
+                                                               max(args.warmup // 2, 2))
+    # leave the sparse state behind for the kernel passes
+    full_prefill(d_eprev, attn_a)
+
+    # per-kernel time of every GEMM class, one profiled step each (events around each launch)
+    kernels = {}
+    for kind in (0, 1, 2, 3, 4, 5, 6):
+        V.vlac_profile_select(ctx, kind)
+        sparse_step()
+        torch.cuda.synchronize()
+        tot, n = V.vlac_profile_read(ctx)
+        if n:
+            epi, cls = kind % 4, kind // 4
+            rows = 1 if cls == 0 else n_rows
+            kernels[kind] = {"name": "gemm_rows<%s> %s" % (KIND_NAMES[epi], CLASS_NAMES[cls]),
+                             "launches_per_step": n, "avg_us": tot / n * 1e3,
+                             "ms_per_step": tot, "bytes": gemm_bytes(cfg, epi, rows)}
+    V.vlac_profile_select(ctx, -1)
+    dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    kd = kernels[dom]
+    achieved = kd["bytes"] / (kd["avg_us"] * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": kd["name"], "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": None, "bytes_per_launch": kd["bytes"],
+                "avg_launch_us": round(kd["avg_us"], 2), "launches_per_step": kd["launches_per_step"]}
+
+    weight_bytes = 2 * nl * (cfg.d_model * (cfg.q_dim + 2 * cfg.kv_dim) + cfg.q_dim * cfg.d_model +
+                             3 * cfg.d_model * cfg.d_ffn)
+    head_bytes = 2 * cfg.vocab * cfg.d_model
+    out = {
+        "metric": "recomputed_token_prefill_tok_per_s",
+        "value": round(n_rows / (ms_prefill * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "c2: OpenVLA-7B shape, 1 stream, 256 visual + 32 text tokens, "
+                               "77/256 patches re-drawn, top-k 180, 7 action tokens",
+                   "n_layers": nl, "rows_recomputed": n_rows, "tokens_reused": n_reused},
+        "step_latency_ms": round(ms_step, 4),
+        "phase_ms": {"select+ratio": round(float(ms_sel), 4), "sparse_prefill": round(float(ms_prefill), 4),
+                     "decode_6_tokens": round(float(ms_decode), 4)},
+        "full_recompute": {"step_latency_ms": round(ms_full_step, 4),
+                           "prefill_ms": round(float(ms_full_prefill), 4),
+                           "prefill_tok_per_s": round(L / (ms_full_prefill * 1e-3), 1)},
+        "speedup_vs_full": {"prefill": round(float(ms_full_prefill / ms_prefill), 3),
+                            "step": round(ms_full_step / ms_step, 3)},
+        "hbm_floor_ms": {"prefill_weights": round((weight_bytes + head_bytes) / (HBM_PEAK_GBS * 1e6), 3),
+                         "decode_weights": round(n_new * (weight_bytes + head_bytes) / (HBM_PEAK_GBS * 1e6), 3)},
+        "step_hbm_frac": round(((1 + n_new) * (weight_bytes + head_bytes) / (ms_step * 1e-3)) / 1e9 / HBM_PEAK_GBS, 4),
+        "kernels": {v["name"]: {"launches_per_step": v["launches_per_step"],
+                                "avg_us": round(v["avg_us"], 2), "ms_per_step": round(v["ms_per_step"], 3),
+                                "GBps": round(v["bytes"] / (v["avg_us"] * 1e-6) / 1e9, 1)}
+                    for v in kernels.values()},
+        "roofline": roofline,
+        "paper_context": "paper: up to 1.7x latency speedup, ~15% control frequency, one RTX 4090, bf16",
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_layers, prev, cur, e_prev, e_cur, patch,
+                                           n_vis, top_k, seed)
+    gm.close()
+    print(json.dumps(out))
+
+
+def cpu_baseline(cfg, n_layers, prev, cur, e_prev, e_cur, patch, n_vis, top_k, seed):
+    """The oracle as it stands, timed on the host: Alg. 1 and the sparse prefill of the
+    same frame pair through the first `n_layers` layers of the same shape; the
+    prefill rate is scaled to the full depth."""
+    import numpy as np
+    import synth
+    from oracle import vlac_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    sub = cfg.with_layers(n_layers)
+    layers = {}
+
+    def layer(l):
+        if l not in layers:
+            layers[l] = {k: v.float().numpy() for k, v in synth.make_layer(sub, seed, l).items()}
+        return layers[l]
+    head = {"g_final": np.ones(cfg.d_model, np.float32),
+            "w_head": np.zeros((32, cfg.d_model), np.float32),
+            "embed": np.zeros((32, cfg.d_model), np.float32)}
+    om = O.Model(sub, layer, head)
+    cache = O.new_cache(sub, 320)
+    O.dense_forward(om, e_prev, n_vis, cache)            # untimed: the state of step t-1
+    t0 = time.perf_counter()
+    p_static = O.select_static(prev, cur, patch, 249, 250, top_k)
+    t1 = time.perf_counter()
+    O.sparse_forward(om, e_cur, n_vis, cache, [p_static] * n_layers)
+    t2 = time.perf_counter()
+    rows = e_cur.shape[0] - len(p_static)
+    prefill_s_full_depth = (t2 - t1) * cfg.n_layers / n_layers
+    return {"value": round(rows / prefill_s_full_depth, 2), "unit": "tokens/s", "cores": int(cores),
+            "kind": "oracle",
+            "sample": "fp64 numpy oracle: Alg. 1 on the frame pair (%.3f s) and the sparse prefill of "
+                      "%d rows through %d of %d layers (%.2f s, scaled x%.1f to full depth)"
+                      % (t1 - t0, rows, n_layers, cfg.n_layers, t2 - t1, cfg.n_layers / n_layers)}
+
+
+if __name__ == "__main__":
+    main()

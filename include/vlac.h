@@ -46,15 +46,24 @@ typedef struct vlac_ctx vlac_ctx;
 
 /* Decoder shape (Sec. 3.1; Llama layout: RMSNorm, rotary embedding in the
  * rotate-half pairing, grouped-query attention, SwiGLU feed-forward).
- * Limits: head_dim is 64 or 128; d_model, n_q_heads*head_dim and d_ffn are
- * multiples of 16; n_q_heads is a multiple of 4 and of n_kv_heads; vocab is a
- * multiple of 32; max_seq is a multiple of 32 and at most 65536. */
+ * Limits: head_dim is 64 or 128; d_model and vocab are multiples of 32, d_ffn of
+ * 16; n_q_heads is a multiple of 4 and of n_kv_heads; max_seq is a multiple of
+ * 32 and at most 65536; max_batch at most 32767. */
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
   float rms_eps, rope_base;
   int32_t max_batch; /* streams (independent environments, each with its own KV cache) */
   int32_t max_seq;   /* cache slots per stream: L + decoded action tokens, rounded up to 32 */
+  int32_t operand_dtype; /* VLAC_OPERAND_BF16 or VLAC_OPERAND_F16, see below */
 } vlac_model_cfg;
+
+/* 16-bit type of the matrix-core operands (weights as stored inside the context,
+ * activations, the KV cache); accumulation, the residual stream, softmax and
+ * norm statistics are fp32 in both modes.  Weights are always handed over as
+ * bf16.  F16 re-encodes them as fp16, which is exact for every bf16 value of
+ * magnitude in [2^-14, 65504], and rounds activations 8 times finer than bf16;
+ * conversions to fp16 saturate at +-65504. */
+enum { VLAC_OPERAND_BF16 = 0, VLAC_OPERAND_F16 = 1 };
 
 /* One decoder layer, device pointers, bf16, row-major [out_features, in_features]
  * (y = x W^T).  wqkv rows: all query heads, then all key heads, then all value
@@ -102,6 +111,17 @@ int vlac_reset_stream(vlac_ctx* ctx, int b, void* kv_cache, void* stream);
  * index it had to ignore (reuse index outside [0, L_v), count larger than the
  * stride): VLAC_E_RANGE once, then cleared.  Kernels never act on such entries. */
 int vlac_check(vlac_ctx* ctx, void* stream);
+
+/* Measurement aid (no part of the method): while a GEMM class is selected, every
+ * launch of that class is bracketed by a pair of HIP events on the launch stream.
+ * kind = epilogue + 4 * row class; epilogue 0 QKV+rotary+cache write, 1 projection
+ * + residual (attention output, FFN down), 2 gate/up + SwiGLU, 3 output head; row
+ * class 0: at most 32 rows (decode, head), 1: more (prefill).  kind -1 switches it off.
+ * vlac_profile_read waits for the recorded launches and returns their summed
+ * elapsed time and their number, then starts counting afresh (at most 2048
+ * launches are recorded between reads). */
+int vlac_profile_select(vlac_ctx* ctx, int kind);
+int vlac_profile_read(vlac_ctx* ctx, double* total_ms, int* launches);
 
 /* Alg. 1 (Sec. 3.2 Eq. sim, Eq. topk; Sec. 3.3 Eq. ptask, Eq. pfinal).
  *

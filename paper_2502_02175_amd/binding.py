@@ -24,7 +24,10 @@ class ModelCfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads",
                                          "head_dim", "d_ffn", "vocab")] + [
         ("rms_eps", C.c_float), ("rope_base", C.c_float),
-        ("max_batch", C.c_int32), ("max_seq", C.c_int32)]
+        ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("operand_dtype", C.c_int32)]
+
+
+OPERAND_BF16, OPERAND_F16 = 0, 1
 
 
 class LayerW(C.Structure):
@@ -56,6 +59,8 @@ def lib():
         L.vlac_set_head_weights.argtypes = [vp, vp, vp, vp, vp]
         L.vlac_reset_stream.argtypes = [vp, i32, vp, vp]
         L.vlac_check.argtypes = [vp, vp]
+        L.vlac_profile_select.argtypes = [vp, i32]
+        L.vlac_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
         L.vlac_select_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, f32,
                                          vp, vp, vp, vp, i32, vp]
         L.vlac_layer_ratio.argtypes = [vp, vp, i32, i32, f32, vp, vp, vp, vp]
@@ -63,6 +68,7 @@ def lib():
         L.vlac_decode_action.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp]
         for name in ("vlac_create", "vlac_destroy", "vlac_last_hip_error", "vlac_set_layer_weights",
                      "vlac_set_head_weights", "vlac_reset_stream", "vlac_check",
+                     "vlac_profile_select", "vlac_profile_read",
                      "vlac_select_static", "vlac_layer_ratio", "vlac_sparse_prefill",
                      "vlac_decode_action"):
             getattr(L, name).restype = i32
@@ -157,6 +163,17 @@ def vlac_reset_stream(ctx, b, kv_cache, stream=None, check=True):
 
 def vlac_check(ctx, stream=None, check=True):
     return _ret(lib().vlac_check(ctx, _stream(stream)), "vlac_check", check)
+
+
+def vlac_profile_select(ctx, kind, check=True):
+    return _ret(lib().vlac_profile_select(ctx, kind), "vlac_profile_select", check)
+
+
+def vlac_profile_read(ctx, check=True):
+    """Returns (total_ms, launches)."""
+    ms, n = C.c_double(), C.c_int()
+    _ret(lib().vlac_profile_read(ctx, C.byref(ms), C.byref(n)), "vlac_profile_read", check)
+    return ms.value, n.value
 
 
 def vlac_select_static(ctx, frame_prev, frame_cur, B, H, W, patch, tau_num, tau_den, top_k,

@@ -32,6 +32,8 @@ int check_cfg(const vlac_model_cfg* m) {
   if (m->n_q_heads % 4 || m->n_q_heads % m->n_kv_heads) return VLAC_E_SHAPE;
   if (m->max_seq > 65536 || m->max_batch > 32767) return VLAC_E_RANGE;
   if (!(m->rms_eps > 0.f) || !(m->rope_base > 1.f)) return VLAC_E_RANGE;
+  if (m->operand_dtype != VLAC_OPERAND_BF16 && m->operand_dtype != VLAC_OPERAND_F16)
+    return VLAC_E_RANGE;
   return VLAC_OK;
 }
 
@@ -48,8 +50,14 @@ void free_all(vlac_ctx* c) {
   void* dev[] = {c->w_head, c->embed, c->g_final, c->rope_cos, c->rope_sin, c->h, c->xa, c->xf,
                  c->qbuf, c->partial, c->counters, c->rows, c->n_rows, c->slot_off, c->rank,
                  c->m_layer, c->n_rows_bl, c->statp, c->stat_counters, c->logits, c->tokens,
-                 c->dec_rows, c->terms, c->flags, c->relevance, c->errword, c->scratch_i};
+                 c->dec_rows, c->terms, c->flags, c->relevance, c->errword, c->scratch_i,
+                 c->zero_tile};
   for (void* p : dev) (void)hipFree(p);
+  for (int i = 0; i < c->prof_cap; ++i) {
+    if (c->prof_start) (void)hipEventDestroy(c->prof_start[i]);
+    if (c->prof_stop) (void)hipEventDestroy(c->prof_stop[i]);
+  }
+  free(c->prof_start); free(c->prof_stop);
   free(c->layer_set); free(c->filled); free(c->was_reset);
   free(c);
 }
@@ -94,6 +102,8 @@ int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out) {
   ctx->kpad_q = round_up(ctx->q_dim, 64);
   ctx->kpad_f = round_up(m.d_ffn, 64);
   ctx->max_rows = m.max_batch * m.max_seq;
+  ctx->prof_kind = -1;
+  ctx->f16 = (m.operand_dtype == VLAC_OPERAND_F16);
   ctx->layers = (LayerW*)calloc(m.n_layers, sizeof(LayerW));
   ctx->layer_set = (uint8_t*)calloc(m.n_layers, 1);
   ctx->filled = (uint8_t*)calloc(m.max_batch, 1);
@@ -143,11 +153,13 @@ int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out) {
   A_(flags, (size_t)mb * 4096);
   A_(relevance, (size_t)mb * 4096);
   A_(errword, 1);
+  A_(zero_tile, 512);
   A_(scratch_i, 64);
 #undef A_
   if (e == hipSuccess) e = hipMemset(ctx->counters, 0, ctx->n_counters * sizeof(int));
   if (e == hipSuccess) e = hipMemset(ctx->stat_counters, 0, mb * sizeof(int));
   if (e == hipSuccess) e = hipMemset(ctx->errword, 0, sizeof(int));
+  if (e == hipSuccess) e = hipMemset(ctx->zero_tile, 0, 512 * sizeof(bf16_t));
   // operand padding (rows of the last 32-row tile, K padding) must be finite: zero once
   if (e == hipSuccess) e = hipMemset(ctx->xa, 0, frag_elems(mr, kpad_x) * sizeof(bf16_t));
   if (e == hipSuccess) e = hipMemset(ctx->xf, 0, frag_elems(mr, ctx->kpad_f) * sizeof(bf16_t));
@@ -198,12 +210,12 @@ int vlac_set_layer_weights(vlac_ctx* ctx, int layer, const vlac_layer_w* w, void
   const vlac_model_cfg& m = ctx->cfg;
   hipStream_t st = (hipStream_t)stream;
   LayerW& L = ctx->layers[layer];
-  launch_pack((const bf16_t*)w->wqkv, ctx->qkv_dim, m.d_model, L.wqkv, ctx->qkv_dim, ctx->kpad_d, 1,
+  launch_pack(ctx->f16, (const bf16_t*)w->wqkv, ctx->qkv_dim, m.d_model, L.wqkv, ctx->qkv_dim, ctx->kpad_d, 1,
               ctx->q_dim, ctx->kv_dim, m.head_dim, st);
-  launch_pack((const bf16_t*)w->wo, m.d_model, ctx->q_dim, L.wo, m.d_model, ctx->kpad_q, 0, 0, 0, 0, st);
-  launch_pack((const bf16_t*)w->w_gate_up, 2 * m.d_ffn, m.d_model, L.wgu, 2 * m.d_ffn, ctx->kpad_d, 2,
+  launch_pack(ctx->f16, (const bf16_t*)w->wo, m.d_model, ctx->q_dim, L.wo, m.d_model, ctx->kpad_q, 0, 0, 0, 0, st);
+  launch_pack(ctx->f16, (const bf16_t*)w->w_gate_up, 2 * m.d_ffn, m.d_model, L.wgu, 2 * m.d_ffn, ctx->kpad_d, 2,
               m.d_ffn, 0, 0, st);
-  launch_pack((const bf16_t*)w->w_down, m.d_model, m.d_ffn, L.wdown, m.d_model, ctx->kpad_f, 0, 0, 0, 0, st);
+  launch_pack(ctx->f16, (const bf16_t*)w->w_down, m.d_model, m.d_ffn, L.wdown, m.d_model, ctx->kpad_f, 0, 0, 0, 0, st);
   launch_bf16_to_f32((const bf16_t*)w->g_attn, L.g_attn, m.d_model, st);
   launch_bf16_to_f32((const bf16_t*)w->g_ffn, L.g_ffn, m.d_model, st);
   VLAC_HIP(hipGetLastError());
@@ -216,7 +228,7 @@ int vlac_set_head_weights(vlac_ctx* ctx, const void* g_final, const void* w_head
   if (!ctx || !g_final || !w_head || !embed) return VLAC_E_NULL;
   const vlac_model_cfg& m = ctx->cfg;
   hipStream_t st = (hipStream_t)stream;
-  launch_pack((const bf16_t*)w_head, m.vocab, m.d_model, ctx->w_head, m.vocab, ctx->kpad_d, 0, 0, 0, 0, st);
+  launch_pack(ctx->f16, (const bf16_t*)w_head, m.vocab, m.d_model, ctx->w_head, m.vocab, ctx->kpad_d, 0, 0, 0, 0, st);
   launch_bf16_to_f32((const bf16_t*)g_final, ctx->g_final, m.d_model, st);
   VLAC_HIP(hipMemcpyAsync(ctx->embed, embed, (size_t)m.vocab * m.d_model * sizeof(bf16_t),
                           hipMemcpyDeviceToDevice, st));
@@ -232,6 +244,40 @@ int vlac_reset_stream(vlac_ctx* ctx, int b, void* kv_cache, void* stream) {
   VLAC_HIP(hipMemsetAsync((char*)kv_cache + (size_t)b * bytes, 0, bytes, (hipStream_t)stream));
   ctx->filled[b] = 0;
   ctx->was_reset[b] = 1;
+  return VLAC_OK;
+}
+
+int vlac_profile_select(vlac_ctx* ctx, int kind) {
+  if (!ctx) return VLAC_E_NULL;
+  if (kind < -1 || kind >= 8) return VLAC_E_RANGE;
+  if (kind >= 0 && !ctx->prof_start) {
+    const int cap = 2048;
+    ctx->prof_start = (hipEvent_t*)calloc(cap, sizeof(hipEvent_t));
+    ctx->prof_stop = (hipEvent_t*)calloc(cap, sizeof(hipEvent_t));
+    if (!ctx->prof_start || !ctx->prof_stop) return VLAC_E_NOMEM;
+    for (int i = 0; i < cap; ++i) {
+      VLAC_HIP(hipEventCreate(&ctx->prof_start[i]));
+      VLAC_HIP(hipEventCreate(&ctx->prof_stop[i]));
+      ctx->prof_cap = i + 1;
+    }
+  }
+  ctx->prof_kind = kind;
+  ctx->prof_n = 0;
+  return VLAC_OK;
+}
+
+int vlac_profile_read(vlac_ctx* ctx, double* total_ms, int* launches) {
+  if (!ctx || !total_ms || !launches) return VLAC_E_NULL;
+  double tot = 0;
+  for (int i = 0; i < ctx->prof_n; ++i) {
+    VLAC_HIP(hipEventSynchronize(ctx->prof_stop[i]));
+    float ms = 0.f;
+    VLAC_HIP(hipEventElapsedTime(&ms, ctx->prof_start[i], ctx->prof_stop[i]));
+    tot += ms;
+  }
+  *total_ms = tot;
+  *launches = ctx->prof_n;
+  ctx->prof_n = 0;
   return VLAC_OK;
 }
 
@@ -297,14 +343,18 @@ int vlac_layer_ratio(vlac_ctx* ctx, const float* attn_mean, int B, int L_v, floa
 namespace {
 
 // One decoder layer over the rows of plane `rows` (count *n_rows <= rows_cap).
+// n_host >= 0: the row count is known on the host; decode_pos >= 0: the rows are
+// (stream b, position decode_pos) for b < n_host, and the row lists are not read.
 void run_layer(vlac_ctx* c, int layer, int B, int rows_cap, int rows_cap_per_stream, int L_v, int L_t,
                const float* resid_in, int resid_stride, const int* rows, const int* n_rows,
-               const int* slot_off, bf16_t* kv, float* out_attn_mean, hipStream_t st) {
+               int n_host, int decode_pos, const int* slot_off, bf16_t* kv, float* out_attn_mean,
+               hipStream_t st) {
   const vlac_model_cfg& m = c->cfg;
   const LayerW& W = c->layers[layer];
   GemmEpi e;
   memset(&e, 0, sizeof(e));
   e.rows = rows;
+  e.decode_pos = decode_pos;
   e.rope_cos = c->rope_cos; e.rope_sin = c->rope_sin;
   e.qbuf = c->qbuf;
   e.kv = kv;
@@ -315,30 +365,31 @@ void run_layer(vlac_ctx* c, int layer, int B, int rows_cap, int rows_cap_per_str
   e.h = c->h; e.d_model = m.d_model;
   e.xf = c->xf; e.kc_f = c->kpad_f / 16; e.d_ffn = m.d_ffn;
 
-  launch_rmsnorm_rows(resid_in, resid_stride, rows, n_rows, rows_cap, W.g_attn, m.rms_eps,
-                      m.d_model, c->xa, c->kpad_d / 16, st);
-  launch_gemm(c, EPI_QKV, W.wqkv, c->qkv_dim / 32, c->kpad_d, c->xa, n_rows, rows_cap, e, st);
-  launch_attention(c, layer, B, rows_cap_per_stream, L_v, L_t, rows, slot_off, kv, out_attn_mean, st);
+  launch_rmsnorm_rows(c->f16, resid_in, resid_stride, rows, n_rows, n_host, decode_pos, rows_cap,
+                      W.g_attn, m.rms_eps, m.d_model, c->xa, c->kpad_d / 16, st);
+  launch_gemm(c, EPI_QKV, W.wqkv, c->qkv_dim / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st);
+  launch_attention(c, layer, B, rows_cap_per_stream, L_v, L_t, rows, slot_off, decode_pos, kv,
+                   out_attn_mean, st);
   e.resid_src = resid_in; e.resid_seq_stride = resid_stride;
-  launch_gemm(c, EPI_RESID, W.wo, m.d_model / 32, c->kpad_q, c->xa, n_rows, rows_cap, e, st);
-  launch_rmsnorm_rows(c->h, m.max_seq, rows, n_rows, rows_cap, W.g_ffn, m.rms_eps, m.d_model, c->xa,
-                      c->kpad_d / 16, st);
-  launch_gemm(c, EPI_SWIGLU, W.wgu, 2 * m.d_ffn / 32, c->kpad_d, c->xa, n_rows, rows_cap, e, st);
+  launch_gemm(c, EPI_RESID, W.wo, m.d_model / 32, c->kpad_q, c->xa, n_rows, n_host, rows_cap, e, st);
+  launch_rmsnorm_rows(c->f16, c->h, m.max_seq, rows, n_rows, n_host, decode_pos, rows_cap, W.g_ffn,
+                      m.rms_eps, m.d_model, c->xa, c->kpad_d / 16, st);
+  launch_gemm(c, EPI_SWIGLU, W.wgu, 2 * m.d_ffn / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st);
   e.resid_src = c->h; e.resid_seq_stride = m.max_seq;
-  launch_gemm(c, EPI_RESID, W.wdown, m.d_model / 32, c->kpad_f, c->xf, n_rows, rows_cap, e, st);
+  launch_gemm(c, EPI_RESID, W.wdown, m.d_model / 32, c->kpad_f, c->xf, n_rows, n_host, rows_cap, e, st);
 }
 
-// Final norm + output head + greedy token for the B rows of plane `rows`.
-void run_head(vlac_ctx* c, int B, const int* rows, const int* n_rows, float* logits,
-              size_t logits_stride, int32_t* out_token, int out_stride, int32_t* token_copy, hipStream_t st) {
+// Final norm + output head + greedy token for the B rows (stream b, position pos).
+void run_head(vlac_ctx* c, int B, int pos, float* logits, size_t logits_stride, int32_t* out_token,
+              int out_stride, int32_t* token_copy, hipStream_t st) {
   const vlac_model_cfg& m = c->cfg;
   GemmEpi e;
   memset(&e, 0, sizeof(e));
-  e.rows = rows;
+  e.decode_pos = pos;
   e.logits = logits; e.vocab = m.vocab; e.logits_stride = logits_stride;
-  launch_rmsnorm_rows(c->h, m.max_seq, rows, n_rows, B, c->g_final, m.rms_eps, m.d_model, c->xa,
-                      c->kpad_d / 16, st);
-  launch_gemm(c, EPI_LOGITS, c->w_head, m.vocab / 32, c->kpad_d, c->xa, n_rows, B, e, st);
+  launch_rmsnorm_rows(c->f16, c->h, m.max_seq, nullptr, nullptr, B, pos, B, c->g_final, m.rms_eps,
+                      m.d_model, c->xa, c->kpad_d / 16, st);
+  launch_gemm(c, EPI_LOGITS, c->w_head, m.vocab / 32, c->kpad_d, c->xa, nullptr, B, B, e, st);
   launch_argmax(logits, logits_stride, B, m.vocab, out_token, out_stride, token_copy, st);
 }
 
@@ -378,15 +429,15 @@ int vlac_sparse_prefill(vlac_ctx* ctx, const float* embeds, int B, int L_v, int 
   for (int l = 0; l < nl; ++l) {
     const int* rows = ctx->rows + (size_t)l * ctx->max_rows;
     run_layer(ctx, l, B, rows_cap, L, L_v, L_t, l == 0 ? embeds : ctx->h, l == 0 ? L : m.max_seq,
-              rows, ctx->n_rows + l, ctx->slot_off + (size_t)l * (m.max_batch + 1),
-              (bf16_t*)kv_cache, out_attn_mean, st);
+              rows, ctx->n_rows + l, reuse_order ? -1 : rows_cap, -1,
+              ctx->slot_off + (size_t)l * (m.max_batch + 1), (bf16_t*)kv_cache, out_attn_mean, st);
   }
   if (out_hidden)
     launch_final_hidden(ctx->h, m.max_seq, ctx->rows + (size_t)(nl - 1) * ctx->max_rows,
                         ctx->n_rows + (nl - 1), rows_cap, ctx->g_final, m.rms_eps, m.d_model,
                         out_hidden, L, st);
-  run_head(ctx, B, ctx->rows + (size_t)nl * ctx->max_rows, ctx->n_rows + nl,
-           out_logits ? out_logits : ctx->logits, (size_t)m.vocab, out_token, 1, nullptr, st);
+  run_head(ctx, B, L - 1, out_logits ? out_logits : ctx->logits, (size_t)m.vocab, out_token, 1,
+           nullptr, st);
   VLAC_HIP(hipGetLastError());
   for (int b = 0; b < B; ++b) ctx->filled[b] = 1;
   return VLAC_OK;
@@ -403,21 +454,14 @@ int vlac_decode_action(vlac_ctx* ctx, int B, int L, int n_new, const int32_t* fi
     if (!ctx->filled[b]) return VLAC_E_STATE;
   if (n_new == 0) return VLAC_OK;
   hipStream_t st = (hipStream_t)stream;
-  launch_decode_plan(ctx, B, L, n_new, st);
-  const int mb = m.max_batch, ms = m.max_seq;
-  const int* rows0 = ctx->dec_rows;
-  const int* n_rows0 = rows0 + (size_t)ms * mb;
-  const int* slot0 = n_rows0 + ms;
+  const int ms = m.max_seq;
   for (int t = 0; t < n_new; ++t) {
-    const int* rows = rows0 + (size_t)t * mb;
-    const int* n_rows = n_rows0 + t;
-    const int* slot_off = slot0 + (size_t)t * (mb + 1);
     launch_embed_rows(ctx->embed, t == 0 ? first_token : ctx->tokens, B, m.d_model, m.vocab, ctx->h,
                       ms, L + t, st);
     for (int l = 0; l < m.n_layers; ++l)
-      run_layer(ctx, l, B, B, 1, 0, 0, ctx->h, ms, rows, n_rows, slot_off, (bf16_t*)kv_cache,
-                nullptr, st);
-    run_head(ctx, B, rows, n_rows, out_logits ? out_logits + (size_t)t * m.vocab : ctx->logits,
+      run_layer(ctx, l, B, B, 1, 0, 0, ctx->h, ms, nullptr, nullptr, B, L + t, nullptr,
+                (bf16_t*)kv_cache, nullptr, st);
+    run_head(ctx, B, L + t, out_logits ? out_logits + (size_t)t * m.vocab : ctx->logits,
              out_logits ? (size_t)n_new * m.vocab : (size_t)m.vocab, out_tokens + t, n_new,
              ctx->tokens, st);
   }

@@ -4,8 +4,10 @@
 // keep last step's, and attention over that partially updated cache is valid;
 // Sec. 3.3, Eq. avistext for the statistic; Sec. 3.1 for the attention itself).
 //
-// One wave handles 32 query rows of one head, flash-style over tiles of 32 cache
-// positions, entirely on the matrix cores and without LDS:
+// A workgroup handles 32 query rows of one head; its 4 waves take every 4th tile
+// of 32 cache positions (so a single decode query still spreads over 4 waves,
+// and a head over its own workgroup), flash-style, entirely on the matrix cores,
+// and merge their (max, sum, output) triples through LDS at the end:
 //   S^T[key, query] = K . Q^T   A operand: K tile (fragment order in the cache),
 //                               B operand: Q tile (fragment order from the QKV epilogue)
 //   O^T[feat, query] += V^T . P^T  A operand: V tile (the cache stores V per 32
@@ -23,12 +25,10 @@
 // counter, no waiting) adds the parked sums over heads and tiles in fixed order.
 #include "common.h"
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
 struct AttnArgs {
   const int* rows;      // this layer's rows (b << 16 | pos)
   const int* slot_off;  // [B + 1] first slot of every stream
+  int decode_pos;       // >= 0: one row per stream at this position; rows / slot_off are not read
   const bf16_t* qbuf;
   bf16_t* out;          // attention output, fragment order, KC = kc_out
   int kc_out;
@@ -44,45 +44,49 @@ struct AttnArgs {
   int* stat_counters;   // [B]
 };
 
-template <int HD>
+template <int HD, bool F16>
 __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a) {
   constexpr int NC = HD / 16;  // k-tiles of a head
   constexpr int NI = HD / 32;  // feature blocks of a head
+  __shared__ float cmb[3][2 + NI * 16][64];  // waves 1..3 park (max, sum, output) here
+  __shared__ float fin[2][64];               // merged max and 1/sum per lane
   __shared__ int s_last;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int j = lane & 31, g = lane >> 5;
-  const int b = blockIdx.z, h = blockIdx.y * 4 + w;
-  const int off_b = a.slot_off[b], n_b = a.slot_off[b + 1] - off_b;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const bool dec = a.decode_pos >= 0;
+  const int off_b = dec ? b : a.slot_off[b];
+  const int n_b = dec ? 1 : a.slot_off[b + 1] - off_b;
   const int s0 = blockIdx.x * 32;
   if (s0 >= n_b) return;
   const int hk = h / (a.n_q_heads / a.n_kv_heads);
   const bool valid = s0 + j < n_b;
   const int sg = off_b + (valid ? s0 + j : n_b - 1);  // this lane's query slot
-  const int pos = valid ? (a.rows[sg] & 0xffff) : 0;
-  const int pos_last = a.rows[off_b + min(s0 + 31, n_b - 1)] & 0xffff;
+  const int pos = dec ? a.decode_pos : (valid ? (a.rows[sg] & 0xffff) : 0);
+  const int pos_last = dec ? a.decode_pos : (a.rows[off_b + min(s0 + 31, n_b - 1)] & 0xffff);
   const int n_kt = (pos_last >> 5) + 1;
 
   const size_t head_elems = (size_t)a.max_seq * HD;
-  const bf16_t* kbase = a.kv + (size_t)b * a.kv_stream_stride + (size_t)hk * head_elems;
+  const bf16_t* kbase = a.kv + (size_t)b * a.kv_stream_stride + (size_t)hk * head_elems +
+                        (size_t)lane * 8;
   const bf16_t* vbase = kbase + (size_t)a.n_kv_heads * head_elems;
 
-  bf16x8 qf[NC];
+  uint4 qf[NC];
   {
     const bf16_t* qsrc = a.qbuf + ((size_t)(sg >> 5) * a.n_q_heads + h) * (size_t)NC * 512 +
                          (size_t)(((sg & 31) + 32 * g) << 3);
 #pragma unroll
-    for (int c = 0; c < NC; ++c) qf[c] = *(const bf16x8*)(qsrc + (size_t)c * 512);
+    for (int c = 0; c < NC; ++c) qf[c] = *(const uint4*)(qsrc + (size_t)c * 512);
   }
-
-  auto scores = [&](int kt, f32x16& s) {
-    const bf16_t* kt_base = kbase + (size_t)kt * NC * 512 + (size_t)lane * 8;
+  auto load_k = [&](int kt, uint4(&kf)[NC]) {
+#pragma unroll
+    for (int c = 0; c < NC; ++c) kf[c] = *(const uint4*)(kbase + ((size_t)kt * NC + c) * 512);
+  };
+  auto scores = [&](const uint4(&kf)[NC], f32x16& s) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const bf16x8 kf = *(const bf16x8*)(kt_base + (size_t)c * 512);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], s, 0, 0, 0);
-    }
+    for (int c = 0; c < NC; ++c) s = mfma32<F16>(kf[c], qf[c], s);
   };
 
   f32x16 o[NI];
@@ -92,9 +96,15 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a) {
     for (int i = 0; i < 16; ++i) o[ib][i] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  for (int kt = 0; kt < n_kt; ++kt) {
+  uint4 kf[NC], kn[NC];
+  if (w < n_kt) load_k(w, kf);
+  for (int kt = w; kt < n_kt; kt += 4) {
     f32x16 s;
-    scores(kt, s);
+    scores(kf, s);
+    uint4 vf[NI * 2];  // this tile's V, and the next tile's K, fly during the softmax arithmetic
+#pragma unroll
+    for (int t = 0; t < NI * 2; ++t) vf[t] = *(const uint4*)(vbase + ((size_t)kt * NI * 2 + t) * 512);
+    if (kt + 4 < n_kt) load_k(kt + 4, kn);
     // register 4*q4 + e of a lane is key 32*kt + 8*q4 + 4*g + e
     float tmax = -INFINITY;
 #pragma unroll
@@ -104,69 +114,96 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a) {
       tmax = fmaxf(tmax, s[i]);
     }
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-    const float m_new = fmaxf(m, tmax);  // finite from tile 0 on: key 0 is visible to every query
-    const float alpha = exp2f(m - m_new);
+    // a tile that lies wholly behind this query leaves max at -inf: keep the state as it is
+    const float m_new = fmaxf(m, tmax);
+    const float alpha = (m_new == -INFINITY) ? 1.f : exp2f(m - m_new);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
     m = m_new;
     float psum = 0.f;
-    float p[16];
+    float pr[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      p[i] = exp2f(s[i] - m_new);
-      psum += p[i];
+      pr[i] = exp2f(s[i] - m_use);
+      psum += pr[i];
     }
     l = l * alpha + psum;
-    bf16x8 pb[2];
+    uint4 pb[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      uint4 u;
-      u.x = pack_bf16x2(p[8 * t + 0], p[8 * t + 1]);
-      u.y = pack_bf16x2(p[8 * t + 2], p[8 * t + 3]);
-      u.z = pack_bf16x2(p[8 * t + 4], p[8 * t + 5]);
-      u.w = pack_bf16x2(p[8 * t + 6], p[8 * t + 7]);
-      pb[t] = __builtin_bit_cast(bf16x8, u);
+      pb[t].x = pack_op2<F16>(pr[8 * t + 0], pr[8 * t + 1]);
+      pb[t].y = pack_op2<F16>(pr[8 * t + 2], pr[8 * t + 3]);
+      pb[t].z = pack_op2<F16>(pr[8 * t + 4], pr[8 * t + 5]);
+      pb[t].w = pack_op2<F16>(pr[8 * t + 6], pr[8 * t + 7]);
     }
-    const bf16_t* vt_base = vbase + (size_t)kt * NI * 2 * 512 + (size_t)lane * 8;
 #pragma unroll
     for (int ib = 0; ib < NI; ++ib) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) o[ib][i] *= alpha;
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const bf16x8 vf = *(const bf16x8*)(vt_base + (size_t)(ib * 2 + t) * 512);
-        o[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[t], o[ib], 0, 0, 0);
-      }
+      for (int t = 0; t < 2; ++t) o[ib] = mfma32<F16>(vf[ib * 2 + t], pb[t], o[ib]);
     }
+#pragma unroll
+    for (int c = 0; c < NC; ++c) kf[c] = kn[c];
   }
   l += __shfl_xor(l, 32);
-  const float inv = 1.f / l;
 
-  if (valid) {
+  // merge the 4 waves (wave 0 owns tile 0, so its max is finite: key 0 is visible to every query)
+  if (w > 0) {
+    cmb[w - 1][0][lane] = m;
+    cmb[w - 1][1][lane] = l;
 #pragma unroll
     for (int ib = 0; ib < NI; ++ib)
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const int f = h * HD + 32 * ib + 8 * q4 + 4 * g;
-        *(uint2*)(a.out + frag_off(sg, f, a.kc_out)) =
-            make_uint2(pack_bf16x2(o[ib][4 * q4] * inv, o[ib][4 * q4 + 1] * inv),
-                       pack_bf16x2(o[ib][4 * q4 + 2] * inv, o[ib][4 * q4 + 3] * inv));
-      }
+      for (int i = 0; i < 16; ++i) cmb[w - 1][2 + ib * 16 + i][lane] = o[ib][i];
+  }
+  __syncthreads();
+  if (w == 0) {
+#pragma unroll
+    for (int ww = 0; ww < 3; ++ww) {
+      const float m_w = cmb[ww][0][lane], l_w = cmb[ww][1][lane];
+      const float m_new = fmaxf(m, m_w);
+      const float a0 = exp2f(m - m_new), a1 = exp2f(m_w - m_new);
+      m = m_new;
+      l = l * a0 + l_w * a1;
+#pragma unroll
+      for (int ib = 0; ib < NI; ++ib)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[ib][i] = o[ib][i] * a0 + cmb[ww][2 + ib * 16 + i][lane] * a1;
+    }
+    const float inv = 1.f / l;
+    fin[0][lane] = m;
+    fin[1][lane] = inv;
+    if (valid) {
+#pragma unroll
+      for (int ib = 0; ib < NI; ++ib)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int f = h * HD + 32 * ib + 8 * q4 + 4 * g;
+          *(uint2*)(a.out + frag_off(sg, f, a.kc_out)) =
+              make_uint2(pack_op2<F16>(o[ib][4 * q4] * inv, o[ib][4 * q4 + 1] * inv),
+                         pack_op2<F16>(o[ib][4 * q4 + 2] * inv, o[ib][4 * q4 + 3] * inv));
+        }
+    }
   }
 
-  // ---- text-to-vision statistic ----
-  if (!a.attn_mean || a.L_t <= 0 || a.L_v <= 0) return;
-  if (pos_last < a.L_v) return;  // no text row in this tile (uniform over the workgroup)
+  // ---- text-to-vision statistic (all conditions are uniform over the workgroup) ----
+  if (!a.attn_mean || a.L_t <= 0 || a.L_v <= 0 || dec) return;
+  if (pos_last < a.L_v) return;  // no text row in this tile
+  __syncthreads();
+  const float m_fin = fin[0][lane], inv_fin = fin[1][lane];
   const int x_first = (n_b - a.L_t) >> 5;  // first tile that holds a text row
   const int n_tt = ((n_b - 1) >> 5) - x_first + 1;
   const int tt = blockIdx.x - x_first;
   const bool is_text = valid && pos >= a.L_v;
   float* park = a.statp + (((size_t)b * a.n_q_heads + h) * a.TT + tt) * a.lv_pad;
   const int n_vt = (a.L_v + 31) >> 5;
-  for (int kt = 0; kt < n_vt; ++kt) {
+  for (int kt = w; kt < n_vt; kt += 4) {
     f32x16 s;
-    scores(kt, s);
+    load_k(kt, kf);
+    scores(kf, s);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      float pv = is_text ? exp2f(s[i] * a.scale_log2e - m) * inv : 0.f;
+      float pv = is_text ? exp2f(s[i] * a.scale_log2e - m_fin) * inv_fin : 0.f;
       // sum over the 32 queries of the tile (the lanes of a half-wave), fixed order
 #pragma unroll
       for (int d = 1; d < 32; d <<= 1) pv += __shfl_xor(pv, d);
@@ -174,37 +211,37 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a) {
     }
     if (j == 0) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) park[32 * kt + 8 * (i >> 2) + 4 * g + (i & 3)] = s[i];
+      for (int i = 0; i < 16; ++i) st_coherent(park + 32 * kt + 8 * (i >> 2) + 4 * g + (i & 3), s[i]);
     }
   }
-  __threadfence();
+  stores_done();
   __syncthreads();
   if (tid == 0) {
-    const int expect = (a.n_q_heads / 4) * n_tt;
+    const int expect = a.n_q_heads * n_tt;
     const int old = atomicAdd(a.stat_counters + b, 1);
     s_last = (old == expect - 1);
     if (old == expect - 1) a.stat_counters[b] = 0;
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
   const float norm = 1.f / ((float)a.n_q_heads * (float)a.L_t);
   for (int v = tid; v < a.L_v; v += 256) {
     float acc = 0.f;
     for (int hh = 0; hh < a.n_q_heads; ++hh)
       for (int t = 0; t < n_tt; ++t)
-        acc += a.statp[(((size_t)b * a.n_q_heads + hh) * a.TT + t) * a.lv_pad + v];
+        acc += ld_coherent(a.statp + (((size_t)b * a.n_q_heads + hh) * a.TT + t) * a.lv_pad + v);
     a.attn_mean[(size_t)b * a.attn_mean_stride + v] = acc * norm;
   }
 }
 
 void launch_attention(vlac_ctx* c, int layer, int B, int rows_cap_per_stream, int L_v, int L_t,
-                      const int* rows, const int* slot_off, bf16_t* kv, float* out_attn_mean,
-                      hipStream_t st) {
+                      const int* rows, const int* slot_off, int decode_pos, bf16_t* kv,
+                      float* out_attn_mean, hipStream_t st) {
   const vlac_model_cfg& m = c->cfg;
   AttnArgs a;
   a.rows = rows;
   a.slot_off = slot_off;
+  a.decode_pos = decode_pos;
   a.qbuf = c->qbuf;
   a.out = c->xa;
   a.kc_out = c->kpad_q / 16;
@@ -223,9 +260,12 @@ void launch_attention(vlac_ctx* c, int layer, int B, int rows_cap_per_stream, in
   a.TT = c->stat_tt;
   a.lv_pad = round_up(L_v > 0 ? L_v : 1, 32);
   a.stat_counters = c->stat_counters;
-  dim3 grid((rows_cap_per_stream + 31) / 32, m.n_q_heads / 4, B);
-  if (m.head_dim == 128)
-    hipLaunchKernelGGL(attn_rows_kernel<128>, grid, dim3(256), 0, st, a);
-  else
-    hipLaunchKernelGGL(attn_rows_kernel<64>, grid, dim3(256), 0, st, a);
+  dim3 grid((rows_cap_per_stream + 31) / 32, m.n_q_heads, B);
+  if (m.head_dim == 128) {
+    if (c->f16) hipLaunchKernelGGL((attn_rows_kernel<128, true>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_rows_kernel<128, false>), grid, dim3(256), 0, st, a);
+  } else {
+    if (c->f16) hipLaunchKernelGGL((attn_rows_kernel<64, true>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_rows_kernel<64, false>), grid, dim3(256), 0, st, a);
+  }
 }

@@ -23,14 +23,57 @@ __host__ __device__ inline size_t frag_off(int row, int col, int KC) {
 static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 #ifdef __HIPCC__
+// Matrix-core operands are 16-bit: bf16 (F16 = false) or IEEE fp16 (F16 = true).
+// The weights arrive as bf16; every bf16 value of ordinary magnitude is exactly
+// representable in fp16 (7 mantissa bits fit in 10), so the fp16 mode only
+// changes how finely the ACTIVATIONS are rounded (2^-11 instead of 2^-8 relative).
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
 __device__ inline bf16_t f2bf(float x) {  // fp32 -> bf16, round to nearest even
   uint32_t u = __float_as_uint(x);
   if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);  // NaN stays NaN
   u += 0x7fffu + ((u >> 16) & 1u);
   return (bf16_t)(u >> 16);
 }
-__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+__device__ inline uint16_t f2h(float x) {  // fp32 -> fp16, round to nearest even, saturating
+  const _Float16 h = (_Float16)fminf(fmaxf(x, -65504.f), 65504.f);
+  return __builtin_bit_cast(uint16_t, h);
+}
+template <bool F16>
+__device__ inline uint16_t f2op(float x) {
+  if constexpr (F16) return f2h(x);
+  else return f2bf(x);
+}
+template <bool F16>
+__device__ inline uint32_t pack_op2(float lo, float hi) {
+  return (uint32_t)f2op<F16>(lo) | ((uint32_t)f2op<F16>(hi) << 16);
+}
+// Hand-over of partial results between workgroups (split-K sums, attention
+// statistics).  The 8 XCDs have one L2 each, and an agent-scope fence
+// (__threadfence) writes back and invalidates a whole L2, which costs more than
+// the kernels it would sit in.  Instead the few words that change hands are
+// written and read with agent-scope atomic accesses, which go through to the
+// memory side and bypass stale lines; a workgroup-scope fence (a plain wait for
+// outstanding stores) orders them before the arrival counter is bumped.
+__device__ inline void st_coherent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float ld_coherent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void stores_done() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+
+// D[32x32] += A[32x16] . B[16x32]; a lane supplies 8 consecutive k of row/col (lane % 32)
+template <bool F16>
+__device__ inline f32x16 mfma32(const uint4& a, const uint4& b, const f32x16& c) {
+  if constexpr (F16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a),
+                                                  __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                   __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 #endif
 
@@ -43,6 +86,7 @@ struct LayerW {
 
 struct vlac_ctx {
   vlac_model_cfg cfg;
+  bool f16;  // operands are fp16 (else bf16)
   int device;
   int last_hip;
   // derived
@@ -80,10 +124,14 @@ struct vlac_ctx {
   uint32_t* terms;  // patch terms [max_batch, 4096, 3]
   uint8_t* flags;   // selection flags
   float* relevance; // [max_batch, 4096]
+  bf16_t* zero_tile; // one operand tile of zeros
   int* errword;     // device error bits
   int* scratch_i;   // small int scratch
   uint8_t* filled;  // host: stream cache holds a prefill
   uint8_t* was_reset;
+  // per-launch timing of one GEMM class (vlac_profile_select)
+  int prof_kind, prof_n, prof_cap;
+  hipEvent_t *prof_start, *prof_stop;
 };
 
 #define VLAC_HIP(call)                         \
@@ -112,9 +160,9 @@ void launch_layer_ratio(const float* attn_mean, int n_layers, int B, int L_v, fl
 void launch_plan(vlac_ctx* c, int B, int L_v, int L_t, const int32_t* reuse_order,
                  const int32_t* reuse_count, int stride, const int32_t* layer_count, hipStream_t st);
 void launch_decode_plan(vlac_ctx* c, int B, int L, int n_new, hipStream_t st);
-void launch_rmsnorm_rows(const float* src, int seq_stride, const int* rows, const int* n_rows,
-                         int max_rows, const float* gain, float eps, int d, bf16_t* xp, int KC,
-                         hipStream_t st);
+void launch_rmsnorm_rows(bool f16, const float* src, int seq_stride, const int* rows,
+                         const int* n_rows, int n_rows_host, int decode_pos, int max_rows, const float* gain, float eps, int d,
+                         bf16_t* xp, int KC, hipStream_t st);
 void launch_final_hidden(const float* src, int seq_stride, const int* rows, const int* n_rows,
                          int max_rows, const float* gain, float eps, int d, float* out, int L,
                          hipStream_t st);
@@ -122,14 +170,15 @@ void launch_argmax(const float* logits, size_t logits_stride, int B, int vocab, 
                    int out_stride, int32_t* out2, hipStream_t st);
 void launch_embed_rows(const bf16_t* embed, const int32_t* tokens, int B, int d, int vocab, float* h,
                        int max_seq, int pos, hipStream_t st);
-void launch_pack(const bf16_t* src, int N, int K, bf16_t* dst, int n_pack, int kpad, int mode,
-                 int p0, int p1, int p2, hipStream_t st);
+void launch_pack(bool to_f16, const bf16_t* src, int N, int K, bf16_t* dst, int n_pack, int kpad,
+                 int mode, int p0, int p1, int p2, hipStream_t st);
 void launch_bf16_to_f32(const bf16_t* src, float* dst, int n, hipStream_t st);
 
 // gemm.hip
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
 struct GemmEpi {
   const int* rows;
+  int decode_pos;  // >= 0: row `slot` is (stream slot, position decode_pos), rows is not read
   // EPI_QKV
   const float *rope_cos, *rope_sin;
   bf16_t* qbuf;
@@ -146,9 +195,9 @@ struct GemmEpi {
 };
 int gemm_init();  // one-time kernel attribute setup; returns hipError_t
 void launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, const bf16_t* xp,
-                 const int* n_rows, int rows_cap, const GemmEpi& e, hipStream_t st);
+                 const int* n_rows, int n_rows_host, int rows_cap, const GemmEpi& e, hipStream_t st);
 
 // attn.hip
 void launch_attention(vlac_ctx* c, int layer, int B, int rows_cap_per_stream, int L_v, int L_t,
-                      const int* rows, const int* slot_off, bf16_t* kv, float* out_attn_mean,
-                      hipStream_t st);
+                      const int* rows, const int* slot_off, int decode_pos, bf16_t* kv,
+                      float* out_attn_mean, hipStream_t st);

@@ -8,14 +8,15 @@
 //
 //  * Weights and activations are both stored in fragment order (common.h), so
 //    every operand fetch is one coalesced 16-byte load per lane and feeds a
-//    v_mfma_f32_32x32x16_bf16 without any shuffling.
+//    v_mfma_f32_32x32x16_{bf16,f16} without any shuffling.
 //  * The matrix-core A operand is the WEIGHT tile (32 output features x 16 k),
 //    the B operand the activation tile (16 k x 32 rows); a lane of the result
 //    holds one row and 4 x 4 consecutive features, which is what the fused
 //    epilogues want (rotary partners, gate/up pairs and packed 8-byte stores in
 //    one lane).
 //  * A workgroup is 4 waves = 4 x 32 output features over all rows of its row
-//    block (MT tiles of 32 rows, accumulators in registers).  Weight tiles go
+//    block (4 tiles of 32 rows, accumulators in registers; more rows = more row
+//    blocks, mapped to the same XCD so that they share the weight tiles in L2).  Weight tiles go
 //    global -> registers (each is used by exactly one wave, LDS would add
 //    nothing); the activation tiles, shared by the 4 waves, are staged through
 //    LDS, double buffered, 64 k per step.
@@ -29,15 +30,14 @@
 //    tile are mapped to the same XCD so that they share its L2.
 #include "common.h"
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
 struct GemmArgs {
   const uint4* wp;    // weights, fragment order, 64 uint4 per tile
   const uint4* xp;    // activations, fragment order
+  const uint4* zero_tile;  // 1 KiB of zeros
   int NB;             // weight row blocks (32 output features each)
   int KS;             // K steps (64 k = 4 tiles each)
   const int* n_rows;  // device: rows in use
+  int n_rows_val;     // >= 0: the row count is known on the host, n_rows is not read
   int S, MB, P;       // split-K factor, row blocks, weight tiles * S
   float* partial;
   int* counters;
@@ -46,7 +46,7 @@ struct GemmArgs {
 
 __device__ inline float silu_f(float x) { return x / (1.f + __expf(-x)); }
 
-template <int EPI>
+template <int EPI, bool F16>
 __device__ inline void epilogue_tile(const GemmEpi& e, int nb, int slot, int id, int g,
                                      const f32x16& acc) {
   const int b = id >> 16, pos = id & 0xffff;
@@ -83,9 +83,9 @@ __device__ inline void epilogue_tile(const GemmEpi& e, int nb, int slot, int id,
         }
         const int f2 = f1 + (hd >> 1);
         *(uint2*)(dst + (size_t)(f1 >> 4) * 512 + ((row + (((f1 >> 3) & 1) << 5)) << 3) + (f1 & 7)) =
-            make_uint2(pack_bf16x2(o1[0], o1[1]), pack_bf16x2(o1[2], o1[3]));
+            make_uint2(pack_op2<F16>(o1[0], o1[1]), pack_op2<F16>(o1[2], o1[3]));
         *(uint2*)(dst + (size_t)(f2 >> 4) * 512 + ((row + (((f2 >> 3) & 1) << 5)) << 3) + (f2 & 7)) =
-            make_uint2(pack_bf16x2(o2[0], o2[1]), pack_bf16x2(o2[2], o2[3]));
+            make_uint2(pack_op2<F16>(o2[0], o2[1]), pack_op2<F16>(o2[2], o2[3]));
       }
     } else {
       // value block -> the cache's V tile: per 32 positions and 32 features, the
@@ -98,7 +98,7 @@ __device__ inline void epilogue_tile(const GemmEpi& e, int nb, int slot, int id,
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4)
 #pragma unroll
-        for (int k = 0; k < 4; ++k) dst[(8 * q4 + 4 * g + k) * 8] = f2bf(acc[4 * q4 + k]);
+        for (int k = 0; k < 4; ++k) dst[(8 * q4 + 4 * g + k) * 8] = f2op<F16>(acc[4 * q4 + k]);
     }
   } else if constexpr (EPI == EPI_RESID) {
     const float* rs = e.resid_src + ((size_t)b * e.resid_seq_stride + pos) * e.d_model + nb * 32 + 4 * g;
@@ -118,7 +118,7 @@ __device__ inline void epilogue_tile(const GemmEpi& e, int nb, int slot, int id,
 #pragma unroll
       for (int k = 0; k < 4; ++k) o[k] = silu_f(acc[4 * q4 + k]) * acc[4 * (q4 + 2) + k];
       *(uint2*)(e.xf + frag_off(slot, ff, e.kc_f)) =
-          make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+          make_uint2(pack_op2<F16>(o[0], o[1]), pack_op2<F16>(o[2], o[3]));
     }
   } else {  // EPI_LOGITS: slot is the stream
     float* out = e.logits + (size_t)slot * e.logits_stride + nb * 32 + 4 * g;
@@ -129,78 +129,96 @@ __device__ inline void epilogue_tile(const GemmEpi& e, int nb, int slot, int id,
   }
 }
 
-template <int MT, int EPI>
-__global__ __launch_bounds__(256) void gemm_rows_kernel(GemmArgs a) {
-  extern __shared__ uint4 lds[];  // [2][MT][256]: two stages of MT activation tiles x 4 k-tiles
-  __shared__ int s_last;
+// Main loop, split-K hand-over and epilogue for a row block with exactly NA active
+// 32-row tiles (a template parameter, so that every loop is unrolled without guards
+// and the compiler can count the loads in flight exactly).
+template <int NA, int MT, int EPI, bool F16>
+__device__ __forceinline__ void rows_body(const GemmArgs& a, uint4* lds, int* s_last, int tile,
+                                          int s, int mb, int n_rows) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  // workgroup id -> (weight tile, split, row block); id % 8 is the XCD
-  const int x = blockIdx.x, y = x >> 3;
-  const int mb = y % a.MB, p = (y / a.MB) * 8 + (x & 7);
-  if (p >= a.P) return;
-  const int tile = p / a.S, s = p - tile * a.S;
-  const int n_rows = *a.n_rows, row0 = mb * MT * 32;
-  if (row0 >= n_rows) return;
-  const int n_act = min(MT, (n_rows - row0 + 31) >> 5);
+  const int row0 = mb * MT * 32;
   const int nb = tile * 4 + w;
   const bool wave_on = nb < a.NB;
   const int KC = 4 * a.KS;
   const int q = a.KS / a.S, r = a.KS % a.S;
-  const int ks0 = s * q + min(s, r), ks1 = ks0 + q + (s < r ? 1 : 0);
-  const uint4* wsrc = a.wp + (size_t)(wave_on ? nb : a.NB - 1) * KC * 64 + lane;
-  const uint4* xsrc = a.xp + (size_t)(row0 >> 5) * KC * 64 + tid;
+  const int ks0 = s * q + min(s, r), n_ks = q + (s < r ? 1 : 0);
+  const uint4* wsrc = a.wp + ((size_t)(wave_on ? nb : a.NB - 1) * KC + 4 * ks0) * 64 + lane;
+  const uint4* xsrc = a.xp + ((size_t)(row0 >> 5) * KC + 4 * ks0) * 64 + tid;
 
-  f32x16 acc[MT];
+  f32x16 acc[NA];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
+  for (int mt = 0; mt < NA; ++mt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
-  uint4 breg[3][4], areg[MT];
+  // Register stages as individually named variables (arrays of them end up in scratch
+  // memory): weight tiles of three steps (B0..B2), activation tiles of two (A0, A1).
+  uint4 B0_0, B0_1, B0_2, B0_3, B1_0, B1_1, B1_2, B1_3, B2_0, B2_1, B2_2, B2_3;
+  uint4 A0_0, A0_1, A0_2, A0_3, A1_0, A1_1, A1_2, A1_3;
+  A0_1 = A0_2 = A0_3 = A1_1 = A1_2 = A1_3 = make_uint4(0, 0, 0, 0);
 
-  auto load_b = [&](int ks, uint4(&dst)[4]) {
-    const int k = min(ks, ks1 - 1);
-#pragma unroll
-    for (int c = 0; c < 4; ++c) dst[c] = wsrc[(size_t)(4 * k + c) * 64];
-  };
-  auto load_a = [&](int ks) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-      if (mt < n_act) areg[mt] = xsrc[((size_t)mt * KC + 4 * ks) * 64];
-  };
-  auto store_a = [&](int buf) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-      if (mt < n_act) lds[(buf * MT + mt) * 256 + tid] = areg[mt];
-  };
-  auto step = [&](int ks, uint4(&bcur)[4]) {
-    const int buf = (ks - ks0) & 1;
-    __syncthreads();
-    const bool more = ks + 1 < ks1;
-    if (more) load_a(ks + 1);
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const bf16x8 bw = __builtin_bit_cast(bf16x8, bcur[c]);
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        if (mt < n_act) {
-          const bf16x8 av = __builtin_bit_cast(bf16x8, lds[(buf * MT + mt) * 256 + c * 64 + lane]);
-          acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw, av, acc[mt], 0, 0, 0);
-        }
-    }
-    load_b(ks + 3, bcur);
-    if (more) store_a(buf ^ 1);
-  };
-
-  load_a(ks0);
-  load_b(ks0, breg[0]);
-  load_b(ks0 + 1, breg[1]);
-  load_b(ks0 + 2, breg[2]);
-  store_a(0);
-  for (int ks = ks0; ks < ks1; ks += 3) {
-    step(ks, breg[0]);
-    if (ks + 1 < ks1) step(ks + 1, breg[1]);
-    if (ks + 2 < ks1) step(ks + 2, breg[2]);
+  // step i of this workgroup covers k-tiles 4i .. 4i+3 of its K range
+#define VLAC_LOAD_B(i, P)                                   \
+  {                                                         \
+    const size_t k_ = (size_t)min((i), n_ks - 1) * 256;     \
+    P##_0 = wsrc[k_];                                       \
+    P##_1 = wsrc[k_ + 64];                                  \
+    P##_2 = wsrc[k_ + 128];                                 \
+    P##_3 = wsrc[k_ + 192];                                 \
   }
+#define VLAC_LOAD_A(i, P)                                             \
+  {                                                                   \
+    const size_t k_ = (size_t)min((i), n_ks - 1) * 256;               \
+    P##_0 = xsrc[k_];                                                 \
+    if constexpr (NA > 1) P##_1 = xsrc[(size_t)KC * 64 + k_];         \
+    if constexpr (NA > 2) P##_2 = xsrc[(size_t)KC * 128 + k_];        \
+    if constexpr (NA > 3) P##_3 = xsrc[(size_t)KC * 192 + k_];        \
+  }
+#define VLAC_STORE_A(buf, P)                                                  \
+  {                                                                           \
+    lds[((buf) * MT + 0) * 256 + tid] = P##_0;                                \
+    if constexpr (NA > 1) lds[((buf) * MT + 1) * 256 + tid] = P##_1;          \
+    if constexpr (NA > 2) lds[((buf) * MT + 2) * 256 + tid] = P##_2;          \
+    if constexpr (NA > 3) lds[((buf) * MT + 3) * 256 + tid] = P##_3;          \
+  }
+#define VLAC_MMA(c, BW)                                                       \
+  _Pragma("unroll") for (int mt = 0; mt < NA; ++mt) acc[mt] =                 \
+      mfma32<F16>(BW, lds[(buf_ * MT + mt) * 256 + (c) * 64 + lane], acc[mt]);
+  // Activation tiles are fetched two steps ahead (registers) and staged one step ahead
+  // (LDS); weight tiles three steps ahead.  Loads return in issue order, so the phases
+  // are fenced against the instruction scheduler.  ACUR held step i (already in LDS).
+#define VLAC_STEP(i, BCUR, ACUR, ANEXT)                                       \
+  {                                                                           \
+    const int buf_ = (i) & 1;                                                 \
+    __syncthreads();                                                          \
+    VLAC_LOAD_A((i) + 2, ACUR)                                                \
+    __builtin_amdgcn_sched_barrier(0);                                        \
+    VLAC_MMA(0, BCUR##_0) VLAC_MMA(1, BCUR##_1) VLAC_MMA(2, BCUR##_2) VLAC_MMA(3, BCUR##_3) \
+    __builtin_amdgcn_sched_barrier(0);                                        \
+    VLAC_LOAD_B((i) + 3, BCUR)                                                \
+    __builtin_amdgcn_sched_barrier(0);                                        \
+    VLAC_STORE_A(buf_ ^ 1, ANEXT)                                             \
+  }
+
+  VLAC_LOAD_A(0, A0)
+  VLAC_LOAD_A(1, A1)
+  VLAC_LOAD_B(0, B0)
+  VLAC_LOAD_B(1, B1)
+  VLAC_LOAD_B(2, B2)
+  __builtin_amdgcn_sched_barrier(0);
+  VLAC_STORE_A(0, A0)
+  for (int i = 0; i < n_ks; i += 6) {
+    VLAC_STEP(i, B0, A0, A1)
+    if (i + 1 < n_ks) VLAC_STEP(i + 1, B1, A1, A0)
+    if (i + 2 < n_ks) VLAC_STEP(i + 2, B2, A0, A1)
+    if (i + 3 < n_ks) VLAC_STEP(i + 3, B0, A1, A0)
+    if (i + 4 < n_ks) VLAC_STEP(i + 4, B1, A0, A1)
+    if (i + 5 < n_ks) VLAC_STEP(i + 5, B2, A1, A0)
+  }
+#undef VLAC_MMA
+#undef VLAC_STEP
+#undef VLAC_STORE_A
+#undef VLAC_LOAD_A
+#undef VLAC_LOAD_B
 
   if (a.S > 1) {
     // split-K: park the partial sums; the last workgroup of this (tile, row block) adds them up
@@ -208,49 +226,175 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(GemmArgs a) {
     float* base = a.partial + ((size_t)(tile * a.MB + mb) * a.S) * 4 * per_wave;
     float* mine = base + ((size_t)s * 4 + w) * per_wave + lane;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-      if (mt < n_act)
+    for (int mt = 0; mt < NA; ++mt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mine[(mt * 16 + i) * 64] = acc[mt][i];
-    __threadfence();
+      for (int i = 0; i < 16; ++i) st_coherent(mine + (mt * 16 + i) * 64, acc[mt][i]);
+    stores_done();
     __syncthreads();
     if (tid == 0) {
       int* cnt = a.counters + tile * a.MB + mb;
       const int old = atomicAdd(cnt, 1);
-      s_last = (old == a.S - 1);
+      *s_last = (old == a.S - 1);
       if (old == a.S - 1) *cnt = 0;  // ready for the next launch
     }
     __syncthreads();
-    if (!s_last) return;
-    __threadfence();
+    if (!*s_last) return;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-      if (mt < n_act)
+    for (int mt = 0; mt < NA; ++mt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          float v = 0.f;
-          for (int ss = 0; ss < a.S; ++ss)
-            v += base[((size_t)ss * 4 + w) * per_wave + (mt * 16 + i) * 64 + lane];
-          acc[mt][i] = v;
-        }
+      for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
+    for (int ss = 0; ss < a.S; ++ss) {  // fixed order; a whole split's worth of loads in flight
+      const float* src = base + ((size_t)ss * 4 + w) * per_wave + lane;
+      float t[NA][16];
+#pragma unroll
+      for (int mt = 0; mt < NA; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) t[mt][i] = ld_coherent(src + (mt * 16 + i) * 64);
+#pragma unroll
+      for (int mt = 0; mt < NA; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[mt][i] += t[mt][i];
+    }
   }
 
   if (!wave_on) return;
   const int g = lane >> 5;
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-    if (mt < n_act) {
-      const int slot = row0 + mt * 32 + (lane & 31);
-      if (slot < n_rows) {
-        const int id = (EPI == EPI_LOGITS) ? 0 : a.e.rows[slot];
-        epilogue_tile<EPI>(a.e, nb, slot, id, g, acc[mt]);
-      }
+  for (int mt = 0; mt < NA; ++mt) {
+    const int slot = row0 + mt * 32 + (lane & 31);
+    if (slot < n_rows) {
+      const int id = (EPI == EPI_LOGITS) ? 0 : a.e.rows[slot];
+      epilogue_tile<EPI, F16>(a.e, nb, slot, id, g, acc[mt]);
     }
+  }
+}
+
+template <int MT, int EPI, bool F16>
+__global__ __launch_bounds__(256) void gemm_rows_kernel(GemmArgs a) {
+  extern __shared__ uint4 lds[];  // [2][MT][256]: two stages of MT activation tiles x 4 k-tiles
+  __shared__ int s_last;
+  // workgroup id -> (weight tile, split, row block); id % 8 is the XCD
+  const int x = blockIdx.x, y = x >> 3;
+  const int mb = y % a.MB, p = (y / a.MB) * 8 + (x & 7);
+  if (p >= a.P) return;
+  const int tile = p / a.S, s = p - tile * a.S;
+  const int n_rows = a.n_rows_val >= 0 ? a.n_rows_val : *a.n_rows;
+  const int row0 = mb * MT * 32;
+  if (row0 >= n_rows) return;
+  static_assert(MT == 4, "row blocks are 4 tiles of 32 rows");
+  switch (min(MT, (n_rows - row0 + 31) >> 5)) {
+    case 1: rows_body<1, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows); break;
+    case 2: rows_body<2, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows); break;
+    case 3: rows_body<3, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows); break;
+    default: rows_body<4, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows); break;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// At most 32 rows (the decode passes, the output head): one 32-feature block
+// per workgroup, the 4 waves split its K range and add up through LDS, so the
+// main loop has no barrier and no LDS traffic at all: every wave streams its
+// own contiguous run of weight tiles, two batches of 8 KiB in flight, and reads
+// the matching activation tiles straight from L2 (only the lanes of real rows
+// load anything).  With S > 1 the K range is also split over S workgroups
+// (N = d_model gives only d/32 blocks); the partial tiles are 4 KiB each.
+// ---------------------------------------------------------------------------
+template <int EPI, bool F16>
+__global__ __launch_bounds__(256) void gemm_few_kernel(GemmArgs a) {
+  __shared__ float red[3][16][64];
+  constexpr int U = 8;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int nb = blockIdx.x / a.S, s = blockIdx.x - nb * a.S;
+  const int n_rows = min(a.n_rows_val >= 0 ? a.n_rows_val : *a.n_rows, 32);
+  if (n_rows <= 0) return;
+  const int KC = 4 * a.KS;
+  const int per = (KC + a.S - 1) / a.S, c_lo = s * per, c_hi = min(KC, c_lo + per);
+  const int perw = (max(c_hi - c_lo, 0) + 3) / 4, w_lo = c_lo + w * perw, w_hi = min(c_hi, w_lo + perw);
+  const uint4* wsrc = a.wp + (size_t)nb * KC * 64 + lane;
+  const uint4* xsrc = a.xp + lane;
+
+  f32x16 acc;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+  uint4 bw[2][U], ax[2][U];
+  // Loads are unconditional and never touch the loaded data (past the end of the range
+  // the weight index is clamped and the activation tile is replaced by a tile of zeros),
+  // so the compiler keeps a whole batch in flight behind the MFMAs.  Lanes of rows >=
+  // n_rows read whatever their operand rows hold; their result columns are never stored.
+  auto load = [&](int c, uint4(&b)[U], uint4(&x)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int cc = max(min(c + u, w_hi - 1), 0);
+      b[u] = wsrc[(size_t)cc * 64];
+      const uint4* xs = (c + u < w_hi) ? xsrc + (size_t)cc * 64 : a.zero_tile + lane;
+      x[u] = *xs;
+    }
+  };
+  auto compute = [&](uint4(&b)[U], uint4(&x)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc = mfma32<F16>(b[u], x[u], acc);
+  };
+  // Loads return in issue order, so the batch a compute phase needs must have been
+  // issued BEFORE the batch that flies behind it; the fences stop the instruction
+  // scheduler from mixing the phases (which would drain the queue every iteration).
+  load(w_lo, bw[0], ax[0]);
+  for (int c = w_lo; c < w_hi; c += 2 * U) {
+    load(c + U, bw[1], ax[1]);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(bw[0], ax[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    load(c + 2 * U, bw[0], ax[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(bw[1], ax[1]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  if (w > 0) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) red[w - 1][i][lane] = acc[i];
+  }
+  __syncthreads();
+  if (w > 0) return;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] += red[0][i][lane] + red[1][i][lane] + red[2][i][lane];
+
+  if (a.S > 1) {  // wave 0 alone hands over / collects the partial tile
+    float* base = a.partial + (size_t)nb * a.S * 1024;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st_coherent(base + (size_t)s * 1024 + i * 64 + lane, acc[i]);
+    stores_done();
+    int last = 0;
+    if (lane == 0) {
+      const int old = atomicAdd(a.counters + nb, 1);
+      last = (old == a.S - 1);
+      if (last) a.counters[nb] = 0;
+    }
+    last = __shfl(last, 0);
+    if (!last) return;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    for (int ss = 0; ss < a.S; ++ss) {  // fixed order, 16 loads in flight
+      float t[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) t[i] = ld_coherent(base + (size_t)ss * 1024 + i * 64 + lane);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[i] += t[i];
+    }
+  }
+  const int slot = lane & 31;
+  if (slot < n_rows) {
+    const int id = (EPI == EPI_LOGITS) ? 0
+                   : (a.e.decode_pos >= 0 ? ((slot << 16) | a.e.decode_pos) : a.e.rows[slot]);
+    epilogue_tile<EPI, F16>(a.e, nb, slot, id, lane >> 5, acc);
+  }
 }
 
 template <int MT, int EPI>
 static hipError_t set_attr() {
-  return hipFuncSetAttribute((const void*)gemm_rows_kernel<MT, EPI>,
+  hipError_t e = hipFuncSetAttribute((const void*)gemm_rows_kernel<MT, EPI, false>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 2 * MT * 4096);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute((const void*)gemm_rows_kernel<MT, EPI, true>,
                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * MT * 4096);
 }
 
@@ -261,55 +405,94 @@ int gemm_init() {
   if ((e = set_attr<MT, EPI_RESID>()) != hipSuccess) return (int)e;     \
   if ((e = set_attr<MT, EPI_SWIGLU>()) != hipSuccess) return (int)e;    \
   if ((e = set_attr<MT, EPI_LOGITS>()) != hipSuccess) return (int)e;
-  VLAC_SET(1) VLAC_SET(4) VLAC_SET(9)
+  VLAC_SET(4)
 #undef VLAC_SET
   return 0;
 }
 
-template <int MT>
+template <int MT, bool F16>
 static void launch_mt(int epi, const GemmArgs& a, int grid, hipStream_t st) {
   const size_t shm = (size_t)2 * MT * 4096;
   switch (epi) {
     case EPI_QKV:
-      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_QKV>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_QKV, F16>), dim3(grid), dim3(256), shm, st, a);
       break;
     case EPI_RESID:
-      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_RESID>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_RESID, F16>), dim3(grid), dim3(256), shm, st, a);
       break;
     case EPI_SWIGLU:
-      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_SWIGLU>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_SWIGLU, F16>), dim3(grid), dim3(256), shm, st, a);
       break;
     default:
-      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_LOGITS>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_LOGITS, F16>), dim3(grid), dim3(256), shm, st, a);
+      break;
+  }
+}
+
+template <bool F16>
+static void launch_few(int epi, const GemmArgs& a, int grid, hipStream_t st) {
+  switch (epi) {
+    case EPI_QKV:
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_QKV, F16>), dim3(grid), dim3(256), 0, st, a);
+      break;
+    case EPI_RESID:
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_RESID, F16>), dim3(grid), dim3(256), 0, st, a);
+      break;
+    case EPI_SWIGLU:
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_SWIGLU, F16>), dim3(grid), dim3(256), 0, st, a);
+      break;
+    default:
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_LOGITS, F16>), dim3(grid), dim3(256), 0, st, a);
       break;
   }
 }
 
 void launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, const bf16_t* xp,
-                 const int* n_rows, int rows_cap, const GemmEpi& e, hipStream_t st) {
+                 const int* n_rows, int n_rows_host, int rows_cap, const GemmEpi& e, hipStream_t st) {
   GemmArgs a;
   a.wp = (const uint4*)wp;
   a.xp = (const uint4*)xp;
+  a.zero_tile = (const uint4*)c->zero_tile;
   a.NB = n_blocks;
   a.KS = kpad / 64;
   a.n_rows = n_rows;
+  a.n_rows_val = n_rows_host;
   a.partial = c->partial;
   a.counters = c->counters;
   a.e = e;
-  const int MT = rows_cap <= 32 ? 1 : (rows_cap <= 128 ? 4 : 9);
-  const int tiles = (n_blocks + 3) / 4;
-  a.MB = (rows_cap + MT * 32 - 1) / (MT * 32);
-  // split K until about two workgroups per CU exist
-  int S = (512 + tiles * a.MB - 1) / (tiles * a.MB);
-  if (S > a.KS) S = a.KS;
-  if (S > 16) S = 16;
-  while (S > 1 && (size_t)tiles * a.MB * S * 4 * MT * 16 * 64 > c->partial_floats) --S;
-  if (tiles * a.MB > c->n_counters) S = 1;
-  if (S < 1) S = 1;
-  a.S = S;
-  a.P = tiles * S;
-  const int grid = ((a.P + 7) / 8) * 8 * a.MB;
-  if (MT == 1) launch_mt<1>(epi, a, grid, st);
-  else if (MT == 4) launch_mt<4>(epi, a, grid, st);
-  else launch_mt<9>(epi, a, grid, st);
+  const int cls = rows_cap <= 32 ? 0 : 1;
+  const bool timed = c->prof_kind == epi + 4 * cls && c->prof_n < c->prof_cap;
+  if (timed) (void)hipEventRecord(c->prof_start[c->prof_n], st);
+  if (cls == 0) {
+    // one workgroup per 32-feature block; K is split over workgroups only when there
+    // are fewer blocks than CUs, and never below 32 k-tiles (8 per wave) per workgroup
+    const int KC = kpad / 16;
+    int S = (256 + n_blocks - 1) / n_blocks;
+    if (S > KC / 32) S = KC / 32;
+    if (S > 8) S = 8;
+    if (S < 1 || n_blocks > c->n_counters || (size_t)n_blocks * 8 * 1024 > c->partial_floats) S = 1;
+    a.S = S;
+    a.MB = 1;
+    a.P = n_blocks * S;
+    if (c->f16) launch_few<true>(epi, a, a.P, st);
+    else launch_few<false>(epi, a, a.P, st);
+  } else {
+    constexpr int MT = 4;
+    const int tiles = (n_blocks + 3) / 4;
+    a.MB = (rows_cap + MT * 32 - 1) / (MT * 32);
+    // split K until about one workgroup per CU exists for ONE row block (the sparse
+    // prefill usually fills one; a full recompute runs several side by side)
+    int S = (256 + tiles - 1) / tiles;
+    if (S > a.KS / 4) S = a.KS / 4;
+    if (S > 8) S = 8;
+    if (S < 1) S = 1;
+    while (S > 1 && (size_t)tiles * a.MB * S * 4 * MT * 16 * 64 > c->partial_floats) --S;
+    if (tiles * a.MB > c->n_counters) S = 1;
+    a.S = S;
+    a.P = tiles * S;
+    const int grid = ((a.P + 7) / 8) * 8 * a.MB;
+    if (c->f16) launch_mt<MT, true>(epi, a, grid, st);
+    else launch_mt<MT, false>(epi, a, grid, st);
+  }
+  if (timed) (void)hipEventRecord(c->prof_stop[c->prof_n++], st);
 }

@@ -161,13 +161,14 @@ __device__ inline float wave_sum(float v) {
   return v;
 }
 
+template <bool F16>
 __global__ __launch_bounds__(256) void rmsnorm_rows_kernel(
     const float* __restrict__ src, int seq_stride, const int* __restrict__ rows,
-    const int* __restrict__ n_rows, const float* __restrict__ gain, float eps, int d,
-    bf16_t* __restrict__ xp, int KC) {
+    const int* __restrict__ n_rows, int n_rows_host, int decode_pos,
+    const float* __restrict__ gain, float eps, int d, bf16_t* __restrict__ xp, int KC) {
   const int slot = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (slot >= *n_rows) return;
-  const int id = rows[slot];
+  if (slot >= (n_rows_host >= 0 ? n_rows_host : *n_rows)) return;
+  const int id = decode_pos >= 0 ? ((slot << 16) | decode_pos) : rows[slot];
   const float* x = src + ((size_t)(id >> 16) * seq_stride + (id & 0xffff)) * d;
   float ss = 0.f;
   for (int k = lane * 4; k < d; k += 256) {
@@ -180,19 +181,23 @@ __global__ __launch_bounds__(256) void rmsnorm_rows_kernel(
     const float4 a = *(const float4*)(x + k), b = *(const float4*)(x + k + 4);
     const float4 ga = *(const float4*)(gain + k), gb = *(const float4*)(gain + k + 4);
     uint4 o;
-    o.x = f2bf(a.x * r * ga.x) | ((uint32_t)f2bf(a.y * r * ga.y) << 16);
-    o.y = f2bf(a.z * r * ga.z) | ((uint32_t)f2bf(a.w * r * ga.w) << 16);
-    o.z = f2bf(b.x * r * gb.x) | ((uint32_t)f2bf(b.y * r * gb.y) << 16);
-    o.w = f2bf(b.z * r * gb.z) | ((uint32_t)f2bf(b.w * r * gb.w) << 16);
+    o.x = pack_op2<F16>(a.x * r * ga.x, a.y * r * ga.y);
+    o.y = pack_op2<F16>(a.z * r * ga.z, a.w * r * ga.w);
+    o.z = pack_op2<F16>(b.x * r * gb.x, b.y * r * gb.y);
+    o.w = pack_op2<F16>(b.z * r * gb.z, b.w * r * gb.w);
     *(uint4*)(xp + frag_off(slot, k, KC)) = o;
   }
 }
 
-void launch_rmsnorm_rows(const float* src, int seq_stride, const int* rows, const int* n_rows,
-                         int max_rows, const float* gain, float eps, int d, bf16_t* xp, int KC,
-                         hipStream_t st) {
-  hipLaunchKernelGGL(rmsnorm_rows_kernel, dim3((max_rows + 3) / 4), dim3(256), 0, st, src,
-                     seq_stride, rows, n_rows, gain, eps, d, xp, KC);
+void launch_rmsnorm_rows(bool f16, const float* src, int seq_stride, const int* rows,
+                         const int* n_rows, int n_rows_host, int decode_pos, int max_rows,
+                         const float* gain, float eps, int d, bf16_t* xp, int KC, hipStream_t st) {
+  if (f16)
+    hipLaunchKernelGGL(rmsnorm_rows_kernel<true>, dim3((max_rows + 3) / 4), dim3(256), 0, st, src,
+                       seq_stride, rows, n_rows, n_rows_host, decode_pos, gain, eps, d, xp, KC);
+  else
+    hipLaunchKernelGGL(rmsnorm_rows_kernel<false>, dim3((max_rows + 3) / 4), dim3(256), 0, st, src,
+                       seq_stride, rows, n_rows, n_rows_host, decode_pos, gain, eps, d, xp, KC);
 }
 
 // Final RMSNorm of every row alive at the last layer, fp32 out [B, L, d].
@@ -292,7 +297,9 @@ void launch_embed_rows(const bf16_t* embed, const int32_t* tokens, int B, int d,
 //           both; value heads keep their order
 //   mode 2  gate/up (p0 = F): every 32-row block holds 16 gate rows followed by
 //           the 16 matching up rows
-// Rows >= n_pack sources and columns >= K are zero.
+// Rows >= n_pack sources and columns >= K are zero.  With to_f16 the bf16 values are
+// re-encoded as fp16 (exact but for magnitudes below 2^-14, which round to
+// multiples of 2^-24).
 // ---------------------------------------------------------------------------
 __device__ inline int pack_src_row(int pr, int mode, int p0, int p1, int p2) {
   if (mode == 1) {
@@ -311,7 +318,7 @@ __device__ inline int pack_src_row(int pr, int mode, int p0, int p1, int p2) {
 __global__ __launch_bounds__(256) void pack_weights_kernel(const bf16_t* __restrict__ src, int N,
                                                            int K, bf16_t* __restrict__ dst,
                                                            int n_pack, int kpad, int mode, int p0,
-                                                           int p1, int p2) {
+                                                           int p1, int p2, int to_f16) {
   const int KC = kpad / 16;
   const size_t n_chunks = (size_t)(n_pack / 32) * KC * 64;  // 16-byte chunks
   for (size_t c = (size_t)blockIdx.x * 256 + threadIdx.x; c < n_chunks;
@@ -324,15 +331,21 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const bf16_t* __restr
     if (col < K) {
       const int sr = pack_src_row(pr, mode, p0, p1, p2);
       if (sr < N) v = *(const uint4*)(src + (size_t)sr * K + col);
+      if (to_f16) {  // bf16 -> fp32 (exact) -> fp16
+        uint32_t* u = (uint32_t*)&v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          u[i] = pack_op2<true>(__uint_as_float(u[i] << 16), __uint_as_float(u[i] & 0xffff0000u));
+      }
     }
     *(uint4*)(dst + c * 8) = v;
   }
 }
 
-void launch_pack(const bf16_t* src, int N, int K, bf16_t* dst, int n_pack, int kpad, int mode,
-                 int p0, int p1, int p2, hipStream_t st) {
+void launch_pack(bool to_f16, const bf16_t* src, int N, int K, bf16_t* dst, int n_pack, int kpad,
+                 int mode, int p0, int p1, int p2, hipStream_t st) {
   hipLaunchKernelGGL(pack_weights_kernel, dim3(2048), dim3(256), 0, st, src, N, K, dst, n_pack,
-                     kpad, mode, p0, p1, p2);
+                     kpad, mode, p0, p1, p2, to_f16 ? 1 : 0);
 }
 
 __global__ void bf16_to_f32_kernel(const bf16_t* __restrict__ src, float* __restrict__ dst, int n) {

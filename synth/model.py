@@ -53,18 +53,21 @@ def round_bf16(x):
     return t.bfloat16().float().numpy()
 
 
-def _gen(seed, *tags):
-    g = torch.Generator(device="cpu")
+def _gen(seed, *tags, device="cpu"):
+    g = torch.Generator(device=device)
     g.manual_seed(int(np.random.SeedSequence([seed, *tags]).generate_state(1)[0]))
     return g
 
 
 def _normal(g, shape, std):
-    return (torch.randn(shape, generator=g, dtype=torch.float32) * std).bfloat16()
+    return (torch.randn(shape, generator=g, dtype=torch.float32, device=g.device) * std).bfloat16()
 
 
-def make_layer(cfg, seed, layer, std=0.02, gain_jitter=0.0):
-    """bf16 torch CPU tensors of one decoder layer.
+def make_layer(cfg, seed, layer, std=0.02, gain_jitter=0.0, device="cpu"):
+    """bf16 torch tensors of one decoder layer.  With device="cpu" (the default) the
+    values are the reference ones every consumer shares; a GPU device draws from that
+    device's generator instead (other values, same distribution; for timing runs
+    that compare nothing against the CPU).
 
     wqkv   [(Hq+2Hkv)*hd, d]  rows: all query heads, then key heads, then value heads
     wo     [d, Hq*hd]
@@ -72,7 +75,7 @@ def make_layer(cfg, seed, layer, std=0.02, gain_jitter=0.0):
     w_down [d, F]
     g_attn, g_ffn [d]         RMSNorm gains (1 + gain_jitter * N(0,1))
     """
-    g = _gen(seed, 1, layer)
+    g = _gen(seed, 1, layer, device=device)
     d, F = cfg.d_model, cfg.d_ffn
     out = {
         "wqkv": _normal(g, (cfg.q_dim + 2 * cfg.kv_dim, d), std),
@@ -81,16 +84,16 @@ def make_layer(cfg, seed, layer, std=0.02, gain_jitter=0.0):
         "w_down": _normal(g, (d, F), std),
     }
     for name in ("g_attn", "g_ffn"):
-        out[name] = (1.0 + gain_jitter * torch.randn(d, generator=g)).bfloat16()
+        out[name] = (1.0 + gain_jitter * torch.randn(d, generator=g, device=g.device)).bfloat16()
     return out
 
 
-def make_head(cfg, seed, std=0.02, gain_jitter=0.0, embed_std=1.0):
+def make_head(cfg, seed, std=0.02, gain_jitter=0.0, embed_std=1.0, device="cpu"):
     """Final norm gain [d], output head [vocab, d], token embedding table [vocab, d]."""
-    g = _gen(seed, 2)
+    g = _gen(seed, 2, device=device)
     d = cfg.d_model
     return {
-        "g_final": (1.0 + gain_jitter * torch.randn(d, generator=g)).bfloat16(),
+        "g_final": (1.0 + gain_jitter * torch.randn(d, generator=g, device=g.device)).bfloat16(),
         "w_head": _normal(g, (cfg.vocab, d), std),
         "embed": _normal(g, (cfg.vocab, d), embed_std),
     }

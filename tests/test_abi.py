@@ -38,7 +38,7 @@ def test_status_strings():
 
 def good_cfg(**kw):
     base = dict(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, d_ffn=688,
-                vocab=256, rms_eps=1e-6, rope_base=1e4, max_batch=2, max_seq=96)
+                vocab=256, rms_eps=1e-6, rope_base=1e4, max_batch=2, max_seq=96, operand_dtype=0)
     base.update(kw)
     return V.ModelCfg(**base)
 
@@ -52,7 +52,7 @@ def test_create_rejects_bad_shapes_on_the_host():
                      (dict(vocab=100), -2), (dict(max_seq=100), -2), (dict(n_q_heads=6), -2),
                      (dict(n_q_heads=8, n_kv_heads=3), -2), (dict(n_layers=0), -3),
                      (dict(max_batch=0), -3), (dict(max_seq=1 << 20), -3), (dict(rms_eps=0.0), -3),
-                     (dict(rope_base=1.0), -3)):
+                     (dict(rope_base=1.0), -3), (dict(operand_dtype=2), -3)):
         cfg = good_cfg(**kw)
         assert lib.vlac_create(C.byref(cfg), C.byref(out)) == want, kw
         assert V.vlac_kv_cache_bytes(cfg) == 0

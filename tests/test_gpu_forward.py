@@ -37,11 +37,11 @@ def check(got, want, b=0, alive=None, stats=True):
     return err_h, err_l
 
 
-@pytest.fixture(scope="module")
-def tiny():
+@pytest.fixture(scope="module", params=["f16", "bf16"])
+def tiny(request):
     prev, cur, redrawn, e_prev, e_cur = tiny_inputs(seed=0)
     om = oracle_model(TINY, seed=0, std=0.05)
-    gm = GpuModel(TINY, seed=0, max_batch=2, max_seq=96, std=0.05)
+    gm = GpuModel(TINY, seed=0, max_batch=2, max_seq=96, std=0.05, operand=request.param)
     yield dict(prev=prev, cur=cur, redrawn=redrawn, e_prev=e_prev, e_cur=e_cur, om=om, gm=gm)
     gm.close()
 
@@ -93,12 +93,13 @@ def test_reuse_list_order_does_not_matter(tiny):
     np.testing.assert_array_equal(a["attn_mean"], b["attn_mean"])
 
 
-def test_batched_streams_gqa_ragged():
+@pytest.mark.parametrize("operand", ["f16", "bf16"])
+def test_batched_streams_gqa_ragged(operand):
     """3 streams with different reuse sets (ragged row counts, several row tiles,
     grouped-query heads, head_dim 128, FFN width that needs K padding)."""
     cfg = GQA_S
     om = oracle_model(cfg, seed=7, std=0.05)
-    gm = GpuModel(cfg, seed=7, max_batch=3, max_seq=160, std=0.05)
+    gm = GpuModel(cfg, seed=7, max_batch=3, max_seq=160, std=0.05, operand=operand)
     try:
         rng = np.random.default_rng(1)
         n_vis, n_txt, B = 100, 37, 3

@@ -14,7 +14,7 @@ TINY = synth.CONFIGS["tiny"]
 def gpu():
     import torch
     import paper_2502_02175_amd as V
-    cfg = V.ModelCfg(4, 256, 4, 4, 64, 688, 256, 1e-6, 1e4, 8, 128)
+    cfg = V.ModelCfg(4, 256, 4, 4, 64, 688, 256, 1e-6, 1e4, 8, 128, V.OPERAND_F16)
     ctx = V.vlac_create(cfg)
     yield dict(V=V, torch=torch, ctx=ctx, n_layers=4)
     V.vlac_destroy(ctx)
