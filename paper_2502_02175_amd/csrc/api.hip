@@ -48,7 +48,7 @@ void free_all(vlac_ctx* c) {
     free(c->layers);
   }
   void* dev[] = {c->w_head, c->embed, c->g_final, c->rope_cos, c->rope_sin, c->h, c->xa, c->xf,
-                 c->qbuf, c->partial, c->counters, c->rows, c->n_rows, c->slot_off, c->rank,
+                 c->qbuf, c->partial, c->rpart, c->counters, c->rows, c->prev_slot, c->n_rows, c->slot_off, c->rank,
                  c->m_layer, c->n_rows_bl, c->statp, c->stat_counters, c->logits, c->tokens,
                  c->dec_rows, c->terms, c->flags, c->relevance, c->errword, c->scratch_i,
                  c->zero_tile};
@@ -116,6 +116,8 @@ int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out) {
   const int nl = m.n_layers, mb = m.max_batch, ms = m.max_seq, mr = ctx->max_rows;
   const int kpad_x = ctx->kpad_d > ctx->kpad_q ? ctx->kpad_d : ctx->kpad_q;
   ctx->partial_floats = (size_t)64 << 20;  // 256 MiB of split-K workspace
+  // partial rows of the projection + residual GEMMs: up to 8 splits of up to 1024 rows
+  ctx->rpart_floats = (size_t)8 * (mr < 1024 ? mr : 1024) * m.d_model;
   ctx->n_counters = 1 << 16;
   ctx->stat_tt = ms / 32 + 1;
 #define A_(ptr, n) if (e == hipSuccess) e = dalloc(&ctx->ptr, (size_t)(n))
@@ -137,8 +139,10 @@ int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out) {
   A_(xf, frag_elems(mr, ctx->kpad_f));
   A_(qbuf, frag_elems(mr, ctx->q_dim));
   A_(partial, ctx->partial_floats);
+  A_(rpart, ctx->rpart_floats);
   A_(counters, ctx->n_counters);
   A_(rows, (size_t)(nl + 1) * mr);
+  A_(prev_slot, (size_t)nl * mr);
   A_(n_rows, nl + 1);
   A_(slot_off, (size_t)(nl + 1) * (mb + 1));
   A_(rank, (size_t)mr);
@@ -345,10 +349,13 @@ namespace {
 // One decoder layer over the rows of plane `rows` (count *n_rows <= rows_cap).
 // n_host >= 0: the row count is known on the host; decode_pos >= 0: the rows are
 // (stream b, position decode_pos) for b < n_host, and the row lists are not read.
+// *pending: split-K factor of partial rows (in c->rpart) that still have to be added
+// to the residual stream c->h: on entry from the previous layer's FFN, on exit from
+// this layer's FFN (0: the residual stream is complete).
 void run_layer(vlac_ctx* c, int layer, int B, int rows_cap, int rows_cap_per_stream, int L_v, int L_t,
                const float* resid_in, int resid_stride, const int* rows, const int* n_rows,
-               int n_host, int decode_pos, const int* slot_off, bf16_t* kv, float* out_attn_mean,
-               hipStream_t st) {
+               int n_host, int decode_pos, const int* slot_off, const int* prev_slot, bf16_t* kv,
+               float* out_attn_mean, int* pending, hipStream_t st) {
   const vlac_model_cfg& m = c->cfg;
   const LayerW& W = c->layers[layer];
   GemmEpi e;
@@ -363,20 +370,49 @@ void run_layer(vlac_ctx* c, int layer, int B, int rows_cap, int rows_cap_per_str
   e.n_q_heads = m.n_q_heads; e.n_kv_heads = m.n_kv_heads; e.head_dim = m.head_dim;
   e.max_seq = m.max_seq;
   e.h = c->h; e.d_model = m.d_model;
+  e.rpart = c->rpart; e.rpart_rows = rows_cap;
   e.xf = c->xf; e.kc_f = c->kpad_f / 16; e.d_ffn = m.d_ffn;
+  const int kc_d = c->kpad_d / 16;
 
-  launch_rmsnorm_rows(c->f16, resid_in, resid_stride, rows, n_rows, n_host, decode_pos, rows_cap,
-                      W.g_attn, m.rms_eps, m.d_model, c->xa, c->kpad_d / 16, st);
-  launch_gemm(c, EPI_QKV, W.wqkv, c->qkv_dim / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st);
+  // decode: the residual rows live in c->h and the RMSNorm is fused into the GEMM
+  const bool fuse = resid_in == c->h && *pending == 0 && gemm_can_fuse_norm(n_host, decode_pos, c->kpad_d);
+  if (fuse) {
+    launch_gemm(c, EPI_QKV, W.wqkv, c->qkv_dim / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st,
+                c->h, W.g_attn);
+  } else {
+    if (*pending)
+      launch_resid_norm_rows(c->f16, c->h, m.max_seq, c->rpart, *pending, rows_cap, c->h, m.max_seq,
+                             rows, prev_slot, n_rows, n_host, rows_cap, W.g_attn, m.rms_eps,
+                             m.d_model, c->xa, kc_d, st);
+    else
+      launch_rmsnorm_rows(c->f16, resid_in, resid_stride, rows, n_rows, n_host, decode_pos, rows_cap,
+                          W.g_attn, m.rms_eps, m.d_model, c->xa, kc_d, st);
+    launch_gemm(c, EPI_QKV, W.wqkv, c->qkv_dim / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st);
+  }
+  *pending = 0;
   launch_attention(c, layer, B, rows_cap_per_stream, L_v, L_t, rows, slot_off, decode_pos, kv,
                    out_attn_mean, st);
   e.resid_src = resid_in; e.resid_seq_stride = resid_stride;
-  launch_gemm(c, EPI_RESID, W.wo, m.d_model / 32, c->kpad_q, c->xa, n_rows, n_host, rows_cap, e, st);
-  launch_rmsnorm_rows(c->f16, c->h, m.max_seq, rows, n_rows, n_host, decode_pos, rows_cap, W.g_ffn,
-                      m.rms_eps, m.d_model, c->xa, c->kpad_d / 16, st);
-  launch_gemm(c, EPI_SWIGLU, W.wgu, 2 * m.d_ffn / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st);
+  const int s_o = launch_gemm(c, EPI_RESID, W.wo, m.d_model / 32, c->kpad_q, c->xa, n_rows, n_host,
+                              rows_cap, e, st);
+  const bool split_o = rows_cap > 32 && s_o > 1;  // the few-rows kernel adds its splits up itself
+  if (fuse) {
+    launch_gemm(c, EPI_SWIGLU, W.wgu, 2 * m.d_ffn / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st,
+                c->h, W.g_ffn);
+  } else {
+    if (split_o)
+      launch_resid_norm_rows(c->f16, resid_in, resid_stride, c->rpart, s_o, rows_cap, c->h, m.max_seq,
+                             rows, nullptr, n_rows, n_host, rows_cap, W.g_ffn, m.rms_eps, m.d_model,
+                             c->xa, kc_d, st);
+    else
+      launch_rmsnorm_rows(c->f16, c->h, m.max_seq, rows, n_rows, n_host, decode_pos, rows_cap, W.g_ffn,
+                          m.rms_eps, m.d_model, c->xa, kc_d, st);
+    launch_gemm(c, EPI_SWIGLU, W.wgu, 2 * m.d_ffn / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st);
+  }
   e.resid_src = c->h; e.resid_seq_stride = m.max_seq;
-  launch_gemm(c, EPI_RESID, W.wdown, m.d_model / 32, c->kpad_f, c->xf, n_rows, n_host, rows_cap, e, st);
+  const int s_d = launch_gemm(c, EPI_RESID, W.wdown, m.d_model / 32, c->kpad_f, c->xf, n_rows, n_host,
+                              rows_cap, e, st);
+  *pending = (rows_cap > 32 && s_d > 1) ? s_d : 0;
 }
 
 // Final norm + output head + greedy token for the B rows (stream b, position pos).
@@ -387,9 +423,14 @@ void run_head(vlac_ctx* c, int B, int pos, float* logits, size_t logits_stride, 
   memset(&e, 0, sizeof(e));
   e.decode_pos = pos;
   e.logits = logits; e.vocab = m.vocab; e.logits_stride = logits_stride;
-  launch_rmsnorm_rows(c->f16, c->h, m.max_seq, nullptr, nullptr, B, pos, B, c->g_final, m.rms_eps,
-                      m.d_model, c->xa, c->kpad_d / 16, st);
-  launch_gemm(c, EPI_LOGITS, c->w_head, m.vocab / 32, c->kpad_d, c->xa, nullptr, B, B, e, st);
+  if (gemm_can_fuse_norm(B, pos, c->kpad_d)) {
+    launch_gemm(c, EPI_LOGITS, c->w_head, m.vocab / 32, c->kpad_d, c->xa, nullptr, B, B, e, st, c->h,
+                c->g_final);
+  } else {
+    launch_rmsnorm_rows(c->f16, c->h, m.max_seq, nullptr, nullptr, B, pos, B, c->g_final, m.rms_eps,
+                        m.d_model, c->xa, c->kpad_d / 16, st);
+    launch_gemm(c, EPI_LOGITS, c->w_head, m.vocab / 32, c->kpad_d, c->xa, nullptr, B, B, e, st);
+  }
   launch_argmax(logits, logits_stride, B, m.vocab, out_token, out_stride, token_copy, st);
 }
 
@@ -426,12 +467,20 @@ int vlac_sparse_prefill(vlac_ctx* ctx, const float* embeds, int B, int L_v, int 
   const int nl = m.n_layers;
   launch_plan(ctx, B, L_v, L_t, reuse_order, reuse_count, stride, layer_count, st);
   const int rows_cap = B * L;
+  const int n_host = reuse_order ? -1 : rows_cap;
+  int pending = 0;
   for (int l = 0; l < nl; ++l) {
     const int* rows = ctx->rows + (size_t)l * ctx->max_rows;
     run_layer(ctx, l, B, rows_cap, L, L_v, L_t, l == 0 ? embeds : ctx->h, l == 0 ? L : m.max_seq,
-              rows, ctx->n_rows + l, reuse_order ? -1 : rows_cap, -1,
-              ctx->slot_off + (size_t)l * (m.max_batch + 1), (bf16_t*)kv_cache, out_attn_mean, st);
+              rows, ctx->n_rows + l, n_host, -1, ctx->slot_off + (size_t)l * (m.max_batch + 1),
+              ctx->prev_slot + (size_t)l * ctx->max_rows, (bf16_t*)kv_cache, out_attn_mean, &pending,
+              st);
   }
+  if (pending)  // the last FFN's partial rows still have to reach the residual stream
+    launch_resid_norm_rows(ctx->f16, ctx->h, m.max_seq, ctx->rpart, pending, rows_cap, ctx->h,
+                           m.max_seq, ctx->rows + (size_t)(nl - 1) * ctx->max_rows, nullptr,
+                           ctx->n_rows + (nl - 1), n_host, rows_cap, nullptr, m.rms_eps, m.d_model,
+                           ctx->xa, ctx->kpad_d / 16, st);
   if (out_hidden)
     launch_final_hidden(ctx->h, m.max_seq, ctx->rows + (size_t)(nl - 1) * ctx->max_rows,
                         ctx->n_rows + (nl - 1), rows_cap, ctx->g_final, m.rms_eps, m.d_model,
@@ -458,9 +507,10 @@ int vlac_decode_action(vlac_ctx* ctx, int B, int L, int n_new, const int32_t* fi
   for (int t = 0; t < n_new; ++t) {
     launch_embed_rows(ctx->embed, t == 0 ? first_token : ctx->tokens, B, m.d_model, m.vocab, ctx->h,
                       ms, L + t, st);
+    int pending = 0;  // at most 32 rows: the few-rows kernel never leaves partial rows behind
     for (int l = 0; l < m.n_layers; ++l)
-      run_layer(ctx, l, B, B, 1, 0, 0, ctx->h, ms, nullptr, nullptr, B, L + t, nullptr,
-                (bf16_t*)kv_cache, nullptr, st);
+      run_layer(ctx, l, B, B, 1, 0, 0, ctx->h, ms, nullptr, nullptr, B, L + t, nullptr, nullptr,
+                (bf16_t*)kv_cache, nullptr, &pending, st);
     run_head(ctx, B, L + t, out_logits ? out_logits + (size_t)t * m.vocab : ctx->logits,
              out_logits ? (size_t)n_new * m.vocab : (size_t)m.vocab, out_tokens + t, n_new,
              ctx->tokens, st);

@@ -107,9 +107,12 @@ struct vlac_ctx {
   bf16_t* qbuf;     // rotated queries, fragment order per head
   float* partial;   // split-K partial sums
   size_t partial_floats;
+  float* rpart;     // split-K partial rows of the projection + residual GEMMs
+  size_t rpart_floats;
   int* counters;    // split-K arrival counters (self-resetting)
   int n_counters;
   int* rows;        // [n_layers + 1][max_rows] (b << 16 | pos); last plane: head rows
+  int* prev_slot;   // [n_layers][max_rows] slot of the same row in the previous layer's list
   int* n_rows;      // [n_layers + 1]
   int* slot_off;    // [n_layers + 1][max_batch + 1]
   int* rank;        // [max_batch][max_seq] position of a token in its reuse order
@@ -163,6 +166,12 @@ void launch_decode_plan(vlac_ctx* c, int B, int L, int n_new, hipStream_t st);
 void launch_rmsnorm_rows(bool f16, const float* src, int seq_stride, const int* rows,
                          const int* n_rows, int n_rows_host, int decode_pos, int max_rows, const float* gain, float eps, int d,
                          bf16_t* xp, int KC, hipStream_t st);
+// h[row] = resid[row] + sum of the S partial rows; optionally RMSNorm(h[row]) -> operand xp
+void launch_resid_norm_rows(bool f16, const float* resid, int resid_seq_stride, const float* part,
+                            int S, int part_rows, float* h, int h_seq_stride, const int* rows,
+                            const int* part_slot, const int* n_rows, int n_rows_host, int max_rows,
+                            const float* gain, float eps, int d, bf16_t* xp, int KC,
+                            hipStream_t st);
 void launch_final_hidden(const float* src, int seq_stride, const int* rows, const int* n_rows,
                          int max_rows, const float* gain, float eps, int d, float* out, int L,
                          hipStream_t st);
@@ -188,14 +197,20 @@ struct GemmEpi {
   // EPI_RESID
   const float* resid_src; int resid_seq_stride;
   float* h; int d_model;
+  float* rpart; int rpart_rows;  // split-K partial rows [split][rpart_rows][d_model]
   // EPI_SWIGLU
   bf16_t* xf; int kc_f; int d_ffn;
   // EPI_LOGITS
   float* logits; int vocab; size_t logits_stride;  // elements between rows
 };
 int gemm_init();  // one-time kernel attribute setup; returns hipError_t
-void launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, const bf16_t* xp,
-                 const int* n_rows, int n_rows_host, int rows_cap, const GemmEpi& e, hipStream_t st);
+// returns the split-K factor used; for EPI_RESID a factor S > 1 means that the result is
+// NOT in the residual stream yet but in e.rpart as S partial rows (launch_resid_norm_rows)
+int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, const bf16_t* xp,
+                 const int* n_rows, int n_rows_host, int rows_cap, const GemmEpi& e, hipStream_t st,
+                 const float* norm_src = nullptr, const float* norm_gain = nullptr);
+// true if launch_gemm may be given norm_src / norm_gain (RMSNorm fused into the GEMM)
+bool gemm_can_fuse_norm(int n_rows_host, int decode_pos, int kpad);
 
 // attn.hip
 void launch_attention(vlac_ctx* c, int layer, int B, int rows_cap_per_stream, int L_v, int L_t,

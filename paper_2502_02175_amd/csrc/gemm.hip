@@ -34,6 +34,12 @@ struct GemmArgs {
   const uint4* wp;    // weights, fragment order, 64 uint4 per tile
   const uint4* xp;    // activations, fragment order
   const uint4* zero_tile;  // 1 KiB of zeros
+  // fused RMSNorm of the input rows (few-rows kernel only): fp32 source rows
+  // [stream, norm_seq_stride, norm_d] at position e.decode_pos, gain, epsilon
+  const float* norm_src;
+  const float* norm_gain;
+  float norm_eps;
+  int norm_d, norm_seq_stride;
   int NB;             // weight row blocks (32 output features each)
   int KS;             // K steps (64 k = 4 tiles each)
   const int* n_rows;  // device: rows in use
@@ -151,10 +157,14 @@ __device__ __forceinline__ void rows_body(const GemmArgs& a, uint4* lds, int* s_
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
   // Register stages as individually named variables (arrays of them end up in scratch
-  // memory): weight tiles of three steps (B0..B2), activation tiles of two (A0, A1).
-  uint4 B0_0, B0_1, B0_2, B0_3, B1_0, B1_1, B1_2, B1_3, B2_0, B2_1, B2_2, B2_3;
-  uint4 A0_0, A0_1, A0_2, A0_3, A1_0, A1_1, A1_2, A1_3;
+  // memory): weight tiles (B0..B3) and activation tiles (A0..A3) of four steps each.
+  // Loads return in issue order, so a tile can only be consumed once everything issued
+  // before it has landed: the L2-resident activation tiles must be fetched as far ahead
+  // as the HBM-resident weight tiles, or they would wait behind them at every step.
+  uint4 B0_0, B0_1, B0_2, B0_3, B1_0, B1_1, B1_2, B1_3, B2_0, B2_1, B2_2, B2_3, B3_0, B3_1, B3_2, B3_3;
+  uint4 A0_0, A0_1, A0_2, A0_3, A1_0, A1_1, A1_2, A1_3, A2_0, A2_1, A2_2, A2_3, A3_0, A3_1, A3_2, A3_3;
   A0_1 = A0_2 = A0_3 = A1_1 = A1_2 = A1_3 = make_uint4(0, 0, 0, 0);
+  A2_1 = A2_2 = A2_3 = A3_1 = A3_2 = A3_3 = make_uint4(0, 0, 0, 0);
 
   // step i of this workgroup covers k-tiles 4i .. 4i+3 of its K range
 #define VLAC_LOAD_B(i, P)                                   \
@@ -183,36 +193,45 @@ __device__ __forceinline__ void rows_body(const GemmArgs& a, uint4* lds, int* s_
 #define VLAC_MMA(c, BW)                                                       \
   _Pragma("unroll") for (int mt = 0; mt < NA; ++mt) acc[mt] =                 \
       mfma32<F16>(BW, lds[(buf_ * MT + mt) * 256 + (c) * 64 + lane], acc[mt]);
-  // Activation tiles are fetched two steps ahead (registers) and staged one step ahead
-  // (LDS); weight tiles three steps ahead.  Loads return in issue order, so the phases
-  // are fenced against the instruction scheduler.  ACUR held step i (already in LDS).
-#define VLAC_STEP(i, BCUR, ACUR, ANEXT)                                       \
+  // Step i: stage slot P held step i (its activation tiles went to LDS during step i-1,
+  // its weight tiles are consumed now) and is refilled with step i+4; the activation
+  // tiles of step i+1 (slot PN) go to the other LDS buffer.  The phases are fenced
+  // against the instruction scheduler so that loads are issued in this order.
+#define VLAC_STEP(i, P, PN)                                                   \
   {                                                                           \
     const int buf_ = (i) & 1;                                                 \
     __syncthreads();                                                          \
-    VLAC_LOAD_A((i) + 2, ACUR)                                                \
+    VLAC_LOAD_A((i) + 4, A##P)                                                \
     __builtin_amdgcn_sched_barrier(0);                                        \
-    VLAC_MMA(0, BCUR##_0) VLAC_MMA(1, BCUR##_1) VLAC_MMA(2, BCUR##_2) VLAC_MMA(3, BCUR##_3) \
+    VLAC_MMA(0, B##P##_0) VLAC_MMA(1, B##P##_1) VLAC_MMA(2, B##P##_2) VLAC_MMA(3, B##P##_3) \
     __builtin_amdgcn_sched_barrier(0);                                        \
-    VLAC_LOAD_B((i) + 3, BCUR)                                                \
+    VLAC_LOAD_B((i) + 4, B##P)                                                \
     __builtin_amdgcn_sched_barrier(0);                                        \
-    VLAC_STORE_A(buf_ ^ 1, ANEXT)                                             \
+    VLAC_STORE_A(buf_ ^ 1, A##PN)                                             \
   }
 
-  VLAC_LOAD_A(0, A0)
-  VLAC_LOAD_A(1, A1)
-  VLAC_LOAD_B(0, B0)
-  VLAC_LOAD_B(1, B1)
-  VLAC_LOAD_B(2, B2)
+  VLAC_LOAD_A(0, A0) VLAC_LOAD_B(0, B0)
+  VLAC_LOAD_A(1, A1) VLAC_LOAD_B(1, B1)
+  VLAC_LOAD_A(2, A2) VLAC_LOAD_B(2, B2)
+  VLAC_LOAD_A(3, A3) VLAC_LOAD_B(3, B3)
   __builtin_amdgcn_sched_barrier(0);
   VLAC_STORE_A(0, A0)
-  for (int i = 0; i < n_ks; i += 6) {
-    VLAC_STEP(i, B0, A0, A1)
-    if (i + 1 < n_ks) VLAC_STEP(i + 1, B1, A1, A0)
-    if (i + 2 < n_ks) VLAC_STEP(i + 2, B2, A0, A1)
-    if (i + 3 < n_ks) VLAC_STEP(i + 3, B0, A1, A0)
-    if (i + 4 < n_ks) VLAC_STEP(i + 4, B1, A0, A1)
-    if (i + 5 < n_ks) VLAC_STEP(i + 5, B2, A1, A0)
+  // Whole groups of 4 steps run in a loop without any branch inside (a conditional step
+  // would make the compiler assume the shortest path around the loop and wait for almost
+  // every load at the top of each iteration); the 0..3 remaining steps follow.
+  int i0 = 0;
+  for (; i0 + 4 <= n_ks; i0 += 4) {
+    VLAC_STEP(i0, 0, 1)
+    VLAC_STEP(i0 + 1, 1, 2)
+    VLAC_STEP(i0 + 2, 2, 3)
+    VLAC_STEP(i0 + 3, 3, 0)
+  }
+  if (i0 < n_ks) {
+    VLAC_STEP(i0, 0, 1)
+    if (i0 + 1 < n_ks) {
+      VLAC_STEP(i0 + 1, 1, 2)
+      if (i0 + 2 < n_ks) VLAC_STEP(i0 + 2, 2, 3)
+    }
   }
 #undef VLAC_MMA
 #undef VLAC_STEP
@@ -220,6 +239,25 @@ __device__ __forceinline__ void rows_body(const GemmArgs& a, uint4* lds, int* s_
 #undef VLAC_LOAD_A
 #undef VLAC_LOAD_B
 
+  if (EPI == EPI_RESID && a.S > 1) {
+    // Projection + residual with split K: every split writes its partial rows
+    // [split][row][feature] and is done; the row kernel that follows (residual add +
+    // RMSNorm) adds the splits up, so nothing is handed over inside this kernel.
+    if (!wave_on) return;
+    const int g = lane >> 5;
+#pragma unroll
+    for (int mt = 0; mt < NA; ++mt) {
+      const int slot = row0 + mt * 32 + (lane & 31);
+      if (slot < n_rows) {
+        float* dst = a.e.rpart + ((size_t)s * a.e.rpart_rows + slot) * a.e.d_model + nb * 32 + 4 * g;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+          *(float4*)(dst + 8 * q4) = make_float4(acc[mt][4 * q4], acc[mt][4 * q4 + 1],
+                                                 acc[mt][4 * q4 + 2], acc[mt][4 * q4 + 3]);
+      }
+    }
+    return;
+  }
   if (a.S > 1) {
     // split-K: park the partial sums; the last workgroup of this (tile, row block) adds them up
     const size_t per_wave = (size_t)MT * 16 * 64;
@@ -298,10 +336,14 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(GemmArgs a) {
 // the matching activation tiles straight from L2 (only the lanes of real rows
 // load anything).  With S > 1 the K range is also split over S workgroups
 // (N = d_model gives only d/32 blocks); the partial tiles are 4 KiB each.
+// NORM: for up to 4 rows the RMSNorm of the input rows is done here as well (every
+// workgroup normalises the rows itself, from L2, while its first weight tiles are
+// in flight), which saves a launch per GEMM in the decode loop.
 // ---------------------------------------------------------------------------
-template <int EPI, bool F16>
+template <int EPI, bool F16, bool NORM>
 __global__ __launch_bounds__(256) void gemm_few_kernel(GemmArgs a) {
   __shared__ float red[3][16][64];
+  extern __shared__ uint4 xlds[];  // NORM: the normalised rows as operand slices [k/8][row]
   constexpr int U = 8;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int nb = blockIdx.x / a.S, s = blockIdx.x - nb * a.S;
@@ -326,26 +368,69 @@ __global__ __launch_bounds__(256) void gemm_few_kernel(GemmArgs a) {
     for (int u = 0; u < U; ++u) {
       const int cc = max(min(c + u, w_hi - 1), 0);
       b[u] = wsrc[(size_t)cc * 64];
-      const uint4* xs = (c + u < w_hi) ? xsrc + (size_t)cc * 64 : a.zero_tile + lane;
-      x[u] = *xs;
+      if constexpr (!NORM) {
+        const uint4* xs = (c + u < w_hi) ? xsrc + (size_t)cc * 64 : a.zero_tile + lane;
+        x[u] = *xs;
+      }
     }
   };
-  auto compute = [&](uint4(&b)[U], uint4(&x)[U]) {
+  auto compute = [&](int c, uint4(&b)[U], uint4(&x)[U]) {
+    if constexpr (NORM) {  // the operand slices come from LDS: [k/8][row], rows < n_rows only
+      const int j = lane & 31, g = lane >> 5;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int cc = max(min(c + u, w_hi - 1), 0);
+        x[u] = (j < n_rows && c + u < w_hi) ? xlds[(cc * 2 + g) * n_rows + j] : make_uint4(0, 0, 0, 0);
+      }
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u) acc = mfma32<F16>(b[u], x[u], acc);
   };
+  // the first two batches of weight tiles fly while the rows are normalised
+  load(w_lo, bw[0], ax[0]);
+  load(w_lo + U, bw[1], ax[1]);
+  __builtin_amdgcn_sched_barrier(0);
+
+  if constexpr (NORM) {
+    // RMSNorm of the (few) rows, fused: x * rsqrt(mean(x^2) + eps) * g, one wave per row
+    const int d = a.norm_d;
+    for (int j = w; j < n_rows; j += 4) {
+      const float* x = a.norm_src + ((size_t)j * a.norm_seq_stride + a.e.decode_pos) * d;
+      float ss = 0.f;
+      for (int k = lane * 4; k < d; k += 256) {
+        const float4 v = *(const float4*)(x + k);
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+      }
+      for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+      const float r = rsqrtf(ss / (float)d + a.norm_eps);
+      for (int k8 = lane; k8 < KC * 2; k8 += 64) {
+        uint4 o = make_uint4(0, 0, 0, 0);
+        if (k8 * 8 < d) {
+          const float4 v0 = *(const float4*)(x + k8 * 8), v1 = *(const float4*)(x + k8 * 8 + 4);
+          const float4 g0 = *(const float4*)(a.norm_gain + k8 * 8);
+          const float4 g1 = *(const float4*)(a.norm_gain + k8 * 8 + 4);
+          o.x = pack_op2<F16>(v0.x * r * g0.x, v0.y * r * g0.y);
+          o.y = pack_op2<F16>(v0.z * r * g0.z, v0.w * r * g0.w);
+          o.z = pack_op2<F16>(v1.x * r * g1.x, v1.y * r * g1.y);
+          o.w = pack_op2<F16>(v1.z * r * g1.z, v1.w * r * g1.w);
+        }
+        xlds[k8 * n_rows + j] = o;
+      }
+    }
+    __syncthreads();
+  }
+
   // Loads return in issue order, so the batch a compute phase needs must have been
   // issued BEFORE the batch that flies behind it; the fences stop the instruction
   // scheduler from mixing the phases (which would drain the queue every iteration).
-  load(w_lo, bw[0], ax[0]);
   for (int c = w_lo; c < w_hi; c += 2 * U) {
-    load(c + U, bw[1], ax[1]);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(bw[0], ax[0]);
+    compute(c, bw[0], ax[0]);
     __builtin_amdgcn_sched_barrier(0);
     load(c + 2 * U, bw[0], ax[0]);
     __builtin_amdgcn_sched_barrier(0);
-    compute(bw[1], ax[1]);
+    compute(c + U, bw[1], ax[1]);
+    __builtin_amdgcn_sched_barrier(0);
+    load(c + 3 * U, bw[1], ax[1]);
     __builtin_amdgcn_sched_barrier(0);
   }
 
@@ -429,26 +514,32 @@ static void launch_mt(int epi, const GemmArgs& a, int grid, hipStream_t st) {
   }
 }
 
-template <bool F16>
-static void launch_few(int epi, const GemmArgs& a, int grid, hipStream_t st) {
+template <bool F16, bool NORM>
+static void launch_few(int epi, const GemmArgs& a, int grid, size_t shm, hipStream_t st) {
   switch (epi) {
     case EPI_QKV:
-      hipLaunchKernelGGL((gemm_few_kernel<EPI_QKV, F16>), dim3(grid), dim3(256), 0, st, a);
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_QKV, F16, NORM>), dim3(grid), dim3(256), shm, st, a);
       break;
     case EPI_RESID:
-      hipLaunchKernelGGL((gemm_few_kernel<EPI_RESID, F16>), dim3(grid), dim3(256), 0, st, a);
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_RESID, F16, NORM>), dim3(grid), dim3(256), shm, st, a);
       break;
     case EPI_SWIGLU:
-      hipLaunchKernelGGL((gemm_few_kernel<EPI_SWIGLU, F16>), dim3(grid), dim3(256), 0, st, a);
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_SWIGLU, F16, NORM>), dim3(grid), dim3(256), shm, st, a);
       break;
     default:
-      hipLaunchKernelGGL((gemm_few_kernel<EPI_LOGITS, F16>), dim3(grid), dim3(256), 0, st, a);
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_LOGITS, F16, NORM>), dim3(grid), dim3(256), shm, st, a);
       break;
   }
 }
 
-void launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, const bf16_t* xp,
-                 const int* n_rows, int n_rows_host, int rows_cap, const GemmEpi& e, hipStream_t st) {
+bool gemm_can_fuse_norm(int n_rows_host, int decode_pos, int kpad) {
+  return n_rows_host >= 1 && n_rows_host <= 4 && decode_pos >= 0 &&
+         (size_t)(kpad / 8) * n_rows_host * 16 <= 40960;
+}
+
+int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, const bf16_t* xp,
+                 const int* n_rows, int n_rows_host, int rows_cap, const GemmEpi& e, hipStream_t st,
+                 const float* norm_src, const float* norm_gain) {
   GemmArgs a;
   a.wp = (const uint4*)wp;
   a.xp = (const uint4*)xp;
@@ -457,6 +548,11 @@ void launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad,
   a.KS = kpad / 64;
   a.n_rows = n_rows;
   a.n_rows_val = n_rows_host;
+  a.norm_src = norm_src;
+  a.norm_gain = norm_gain;
+  a.norm_eps = c->cfg.rms_eps;
+  a.norm_d = c->cfg.d_model;
+  a.norm_seq_stride = c->cfg.max_seq;
   a.partial = c->partial;
   a.counters = c->counters;
   a.e = e;
@@ -474,8 +570,14 @@ void launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad,
     a.S = S;
     a.MB = 1;
     a.P = n_blocks * S;
-    if (c->f16) launch_few<true>(epi, a, a.P, st);
-    else launch_few<false>(epi, a, a.P, st);
+    if (norm_src) {  // only offered when gemm_can_fuse_norm() holds
+      const size_t shm = (size_t)(kpad / 8) * n_rows_host * 16;
+      if (c->f16) launch_few<true, true>(epi, a, a.P, shm, st);
+      else launch_few<false, true>(epi, a, a.P, shm, st);
+    } else {
+      if (c->f16) launch_few<true, false>(epi, a, a.P, 0, st);
+      else launch_few<false, false>(epi, a, a.P, 0, st);
+    }
   } else {
     constexpr int MT = 4;
     const int tiles = (n_blocks + 3) / 4;
@@ -486,8 +588,12 @@ void launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad,
     if (S > a.KS / 4) S = a.KS / 4;
     if (S > 8) S = 8;
     if (S < 1) S = 1;
-    while (S > 1 && (size_t)tiles * a.MB * S * 4 * MT * 16 * 64 > c->partial_floats) --S;
-    if (tiles * a.MB > c->n_counters) S = 1;
+    if (epi == EPI_RESID) {
+      while (S > 1 && (size_t)S * e.rpart_rows * e.d_model > c->rpart_floats) --S;
+    } else {
+      while (S > 1 && (size_t)tiles * a.MB * S * 4 * MT * 16 * 64 > c->partial_floats) --S;
+      if (tiles * a.MB > c->n_counters) S = 1;
+    }
     a.S = S;
     a.P = tiles * S;
     const int grid = ((a.P + 7) / 8) * 8 * a.MB;
@@ -495,4 +601,5 @@ void launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad,
     else launch_mt<MT, false>(epi, a, grid, st);
   }
   if (timed) (void)hipEventRecord(c->prof_stop[c->prof_n++], st);
+  return a.S;
 }

@@ -73,9 +73,9 @@ __global__ __launch_bounds__(256) void plan_rows_kernel(
     int L_v, int L_t, int n_layers, int max_seq, int max_rows, int max_batch,
     const int* __restrict__ rank, const int* __restrict__ m_layer,
     const int* __restrict__ n_rows_bl, int B, int* __restrict__ rows, int* __restrict__ n_rows,
-    int* __restrict__ slot_off) {
-  __shared__ int wsum[4];
-  __shared__ int base_s;
+    int* __restrict__ slot_off, int* __restrict__ prev_slot) {
+  __shared__ int wsum[4], wsum_p[4];
+  __shared__ int base_s, base_p;
   const int l = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int L = L_v + L_t;
   if (l == n_layers) {
@@ -89,8 +89,11 @@ __global__ __launch_bounds__(256) void plan_rows_kernel(
     }
     return;
   }
-  int off = 0;
-  for (int k = 0; k < b; ++k) off += n_rows_bl[(size_t)l * B + k];
+  int off = 0, off_p = 0;  // first slot of this stream at this layer / at the layer before
+  for (int k = 0; k < b; ++k) {
+    off += n_rows_bl[(size_t)l * B + k];
+    if (l > 0) off_p += n_rows_bl[(size_t)(l - 1) * B + k];
+  }
   if (tid == 0) {
     slot_off[(size_t)l * (max_batch + 1) + b] = off;
     if (b == B - 1) {
@@ -99,22 +102,33 @@ __global__ __launch_bounds__(256) void plan_rows_kernel(
       n_rows[l] = tot;
     }
     base_s = off;
+    base_p = off_p;
   }
   __syncthreads();
   const int m = m_layer[(size_t)b * n_layers + l];
+  const int m_p = l > 0 ? m_layer[(size_t)b * n_layers + l - 1] : 0;  // m is non-decreasing over l
   const int* rk = rank + (size_t)b * max_seq;
   for (int c0 = 0; c0 < L; c0 += 256) {
     const int p = c0 + tid;
     const int keep = p < L && !(p < L_v && rk[p] < m);
-    const unsigned long long bal = __ballot(keep);
-    const int inwave = __popcll(bal & ((1ull << lane) - 1ull));
-    if (lane == 0) wsum[w] = __popcll(bal);
+    const int keep_p = p < L && !(p < L_v && rk[p] < m_p);  // row of the layer before (a superset)
+    const unsigned long long bal = __ballot(keep), bal_p = __ballot(keep_p);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    const int inwave = __popcll(bal & below), inwave_p = __popcll(bal_p & below);
+    if (lane == 0) { wsum[w] = __popcll(bal); wsum_p[w] = __popcll(bal_p); }
     __syncthreads();
-    int o = base_s;
-    for (int k = 0; k < w; ++k) o += wsum[k];
-    if (keep) rows[(size_t)l * max_rows + o + inwave] = (b << 16) | p;
+    int o = base_s, o_p = base_p;
+    for (int k = 0; k < w; ++k) { o += wsum[k]; o_p += wsum_p[k]; }
+    if (keep) {
+      rows[(size_t)l * max_rows + o + inwave] = (b << 16) | p;
+      // where the same row sat in the previous layer's list (its FFN partial rows are there)
+      prev_slot[(size_t)l * max_rows + o + inwave] = l > 0 ? o_p + inwave_p : o + inwave;
+    }
     __syncthreads();
-    if (tid == 0) base_s += wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    if (tid == 0) {
+      base_s += wsum[0] + wsum[1] + wsum[2] + wsum[3];
+      base_p += wsum_p[0] + wsum_p[1] + wsum_p[2] + wsum_p[3];
+    }
     __syncthreads();
   }
 }
@@ -128,7 +142,7 @@ void launch_plan(vlac_ctx* c, int B, int L_v, int L_t, const int32_t* reuse_orde
                      c->n_rows_bl, B, c->errword);
   hipLaunchKernelGGL(plan_rows_kernel, dim3(nl + 1, B), dim3(256), 0, st, L_v, L_t, nl,
                      c->cfg.max_seq, c->max_rows, c->cfg.max_batch, c->rank, c->m_layer,
-                     c->n_rows_bl, B, c->rows, c->n_rows, c->slot_off);
+                     c->n_rows_bl, B, c->rows, c->n_rows, c->slot_off, c->prev_slot);
 }
 
 // Decode row lists: plane t (0 <= t < n_new) holds row (b, L + t) for every stream.
@@ -198,6 +212,64 @@ void launch_rmsnorm_rows(bool f16, const float* src, int seq_stride, const int* 
   else
     hipLaunchKernelGGL(rmsnorm_rows_kernel<false>, dim3((max_rows + 3) / 4), dim3(256), 0, st, src,
                        seq_stride, rows, n_rows, n_rows_host, decode_pos, gain, eps, d, xp, KC);
+}
+
+// Residual add with the split-K partial rows of the projection that came before, then
+// (optionally) the RMSNorm that comes next: h[row] = resid[row] + sum_s part[s][slot];
+// xp[slot] = RMSNorm(h[row]) * gain.  One workgroup per row (S + 1 independent 16-byte
+// loads per thread and pass keep the memory system busy; the work per row is all
+// latency); a thread re-reads only what it wrote itself.  gain == nullptr: no norm.
+template <bool F16>
+__global__ __launch_bounds__(256) void resid_norm_rows_kernel(
+    const float* __restrict__ resid, int resid_seq_stride, const float* __restrict__ part, int S,
+    int part_rows, float* __restrict__ h, int h_seq_stride, const int* __restrict__ rows,
+    const int* __restrict__ part_slot, const int* __restrict__ n_rows, int n_rows_host,
+    const float* __restrict__ gain, float eps, int d, bf16_t* __restrict__ xp, int KC) {
+  __shared__ float red[4];
+  const int slot = blockIdx.x, tid = threadIdx.x;
+  if (slot >= (n_rows_host >= 0 ? n_rows_host : *n_rows)) return;
+  const int id = rows[slot];
+  const float* r = resid + ((size_t)(id >> 16) * resid_seq_stride + (id & 0xffff)) * d;
+  float* y = h + ((size_t)(id >> 16) * h_seq_stride + (id & 0xffff)) * d;
+  // the partial rows are indexed by the slot the row had when the GEMM ran
+  const float* p0 = part + (size_t)(part_slot ? part_slot[slot] : slot) * d;
+  const size_t pstride = (size_t)part_rows * d;
+  float ss = 0.f;
+  for (int k = tid * 4; k < d; k += 1024) {
+    float4 v = *(const float4*)(r + k);
+    for (int s = 0; s < S; ++s) {  // fixed order
+      const float4 q = *(const float4*)(p0 + (size_t)s * pstride + k);
+      v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
+    }
+    *(float4*)(y + k) = v;
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  if (!gain) return;
+  ss = wave_sum(ss);
+  if ((tid & 63) == 0) red[tid >> 6] = ss;
+  __syncthreads();
+  const float rinv = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
+  for (int k = tid * 4; k < d; k += 1024) {
+    const float4 v = *(const float4*)(y + k), g = *(const float4*)(gain + k);
+    *(uint2*)(xp + frag_off(slot, k, KC)) =
+        make_uint2(pack_op2<F16>(v.x * rinv * g.x, v.y * rinv * g.y),
+                   pack_op2<F16>(v.z * rinv * g.z, v.w * rinv * g.w));
+  }
+}
+
+void launch_resid_norm_rows(bool f16, const float* resid, int resid_seq_stride, const float* part,
+                            int S, int part_rows, float* h, int h_seq_stride, const int* rows,
+                            const int* part_slot, const int* n_rows, int n_rows_host, int max_rows,
+                            const float* gain, float eps, int d, bf16_t* xp, int KC,
+                            hipStream_t st) {
+  if (f16)
+    hipLaunchKernelGGL(resid_norm_rows_kernel<true>, dim3(max_rows), dim3(256), 0, st,
+                       resid, resid_seq_stride, part, S, part_rows, h, h_seq_stride, rows, part_slot,
+                       n_rows, n_rows_host, gain, eps, d, xp, KC);
+  else
+    hipLaunchKernelGGL(resid_norm_rows_kernel<false>, dim3(max_rows), dim3(256), 0, st,
+                       resid, resid_seq_stride, part, S, part_rows, h, h_seq_stride, rows, part_slot,
+                       n_rows, n_rows_host, gain, eps, d, xp, KC);
 }
 
 // Final RMSNorm of every row alive at the last layer, fp32 out [B, L, d].

@@ -123,3 +123,87 @@ def test_7b_full_depth_properties():
         torch.cuda.empty_cache()
     finally:
         gm.close()
+
+
+def _random_streams(cfg, B, n_vis, n_txt, static_frac, seed):
+    """Embeddings of two consecutive steps for B streams: a fraction of the visual
+    tokens keeps its embedding, the rest is re-drawn."""
+    rng = np.random.default_rng(seed)
+    L_ = n_vis + n_txt
+    e0 = synth.round_bf16(rng.standard_normal((B, L_, cfg.d_model)))
+    e1 = e0.copy()
+    changed = rng.random((B, n_vis)) >= static_frac
+    e1[:, :n_vis][changed] = synth.round_bf16(rng.standard_normal((int(changed.sum()), cfg.d_model)))
+    return e0, e1, changed
+
+
+def _check_streams(cfg, B, n_vis, n_txt, static_frac, seed, n_new, tol=2e-2):
+    om = oracle_model(cfg, seed=seed, gain_jitter=0.1)
+    L_ = n_vis + n_txt
+    max_seq = (L_ + n_new + 31) // 32 * 32
+    gm = GpuModel(cfg, seed=seed, max_batch=B, max_seq=max_seq, gain_jitter=0.1)
+    try:
+        e0, e1, changed = _random_streams(cfg, B, n_vis, n_txt, static_frac, seed)
+        caches = [O.new_cache(cfg, max_seq) for _ in range(B)]
+        want0 = [O.dense_forward(om, e0[b], n_vis, caches[b]) for b in range(B)]
+        got0 = gm.prefill(e0, n_vis)
+        for b in range(B):
+            assert np.abs(got0["hidden"][b] - want0[b]["hidden"]).max() <= tol
+            assert np.abs(got0["logits"][b] - want0[b]["logits"]).max() <= tol
+            np.testing.assert_allclose(got0["attn_mean"][:, b], want0[b]["attn_mean"], atol=1e-4, rtol=2e-2)
+        reuse = [np.flatnonzero(~changed[b]).tolist() for b in range(B)]
+        want1 = [O.sparse_forward(om, e1[b], n_vis, caches[b], [reuse[b]] * cfg.n_layers) for b in range(B)]
+        got1 = gm.prefill(e1, n_vis, reuse)
+        for b in range(B):
+            alive = ~np.isnan(want1[b]["hidden"][:, 0])
+            assert np.abs(got1["hidden"][b][alive] - want1[b]["hidden"][alive]).max() <= tol
+            assert np.all(np.isnan(got1["hidden"][b][~alive]))
+            assert np.abs(got1["logits"][b] - want1[b]["logits"]).max() <= tol
+            np.testing.assert_allclose(got1["attn_mean"][:, b], want1[b]["attn_mean"], atol=1e-4, rtol=2e-2)
+            if margin(want1[b]["logits"]) > 2 * tol:
+                assert int(got1["token"][b]) == want1[b]["token"]
+        first = [w["token"] for w in want1]
+        gt, gl = gm.decode(B, L_, n_new, first)
+        for b in range(B):
+            toks, logits = O.decode(om, caches[b], L_, first[b], n_new, return_logits=True)
+            assert np.abs(gl[b] - logits).max() <= tol
+            if all(margin(x) > 2 * tol for x in logits):
+                assert gt[b].tolist() == toks
+    finally:
+        gm.close()
+
+
+def test_hires_batched_shape_against_oracle():
+    """High-resolution batched shape: 7B layer dims, 1024 visual + 32 text tokens per
+    stream, 70% static; 2 streams and 1 layer keep the oracle within seconds.  Many
+    row blocks per GEMM, 33 key tiles per query, a 1024-wide attention statistic."""
+    _check_streams(CFG.with_layers(1), B=2, n_vis=1024, n_txt=32, static_frac=0.7, seed=3, n_new=1)
+
+
+def test_gqa_batched_shape_against_oracle():
+    """Grouped-query shape: d 1536, 12 query / 2 kv heads x 128, FFN 8960, rope base 1e6,
+    256 visual + 48 text tokens, 75% static; 8 streams x 2 layers against the oracle."""
+    _check_streams(synth.CONFIGS["gqa"].with_layers(2), B=8, n_vis=256, n_txt=48, static_frac=0.75,
+                   seed=4, n_new=2)
+
+
+def test_gqa_32_streams_properties():
+    """The grouped-query configuration at its full batch of 32 streams and 28 layers
+    (weights drawn on the GPU): identical frames => the sparse prefill with 75% of the
+    visual tokens reused equals the full recompute bit for bit, stream by stream."""
+    cfg = synth.CONFIGS["gqa"]
+    B, n_vis, n_txt = 32, 256, 48
+    gm = GpuModel(cfg, seed=5, max_batch=B, max_seq=320, gain_jitter=0.1, gen_device="cuda:0")
+    try:
+        e0, _, changed = _random_streams(cfg, B, n_vis, n_txt, 0.75, seed=5)
+        full = gm.prefill(e0, n_vis, want_hidden=False)
+        t_full, _ = gm.decode(B, n_vis + n_txt, 6, full["token"])
+        assert np.isfinite(full["logits"]).all()
+        reuse = [np.flatnonzero(~changed[b]).tolist() for b in range(B)]
+        same = gm.prefill(e0, n_vis, reuse, want_hidden=False)
+        np.testing.assert_array_equal(same["logits"], full["logits"])
+        np.testing.assert_allclose(same["attn_mean"], full["attn_mean"], rtol=1e-4, atol=1e-8)
+        t_same, _ = gm.decode(B, n_vis + n_txt, 6, same["token"])
+        np.testing.assert_array_equal(t_same, t_full)
+    finally:
+        gm.close()

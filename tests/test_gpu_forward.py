@@ -137,6 +137,49 @@ def test_batched_streams_gqa_ragged(operand):
         gm.close()
 
 
+def test_mid_size_split_k_with_layer_varying_reuse():
+    """d = 1024: the projection GEMMs split K over workgroups and hand partial rows to the
+    next row kernel; with reuse counts that grow over depth the row lists of consecutive
+    layers differ, so the partial rows must be found through the previous layer's slots.
+    Also 6 streams: the decode/head path without the fused norm (more than 4 rows)."""
+    cfg = synth.ModelCfg(4, 1024, 8, 8, 128, 2752, 512)
+    om = oracle_model(cfg, seed=11, std=0.03)
+    gm = GpuModel(cfg, seed=11, max_batch=6, max_seq=128, std=0.03)
+    try:
+        rng = np.random.default_rng(2)
+        n_vis, n_txt, B = 80, 20, 6
+        L = n_vis + n_txt
+        e0 = synth.round_bf16(rng.standard_normal((B, L, cfg.d_model)))
+        e1 = e0.copy()
+        changed = rng.random((B, n_vis)) < 0.25
+        e1[:, :n_vis][changed] = synth.round_bf16(rng.standard_normal((int(changed.sum()), cfg.d_model)))
+        caches = [O.new_cache(cfg, 128) for _ in range(B)]
+        for b in range(B):
+            O.dense_forward(om, e0[b], n_vis, caches[b])
+        gm.prefill(e0, n_vis, want_stats=False, want_hidden=False)
+        orders, counts, sets = [], [], []
+        for b in range(B):
+            static = np.flatnonzero(~changed[b]).tolist()
+            rng.shuffle(static)
+            n = len(static)
+            m = [0, n // 4 + b, n // 2, n] if b % 2 == 0 else [n // 3, n // 3, n - 1, n - 1]
+            orders.append(static), counts.append(m)
+            sets.append([static[:k] for k in m])
+        want = [O.sparse_forward(om, e1[b], n_vis, caches[b], sets[b]) for b in range(B)]
+        got = gm.prefill(e1, n_vis, orders, counts)
+        for b in range(B):
+            check(got, want[b], b)
+        first = [w["token"] for w in want]
+        gt, gl = gm.decode(B, L, 2, first)
+        for b in range(B):
+            toks, logits = O.decode(om, caches[b], L, first[b], 2, return_logits=True)
+            assert np.abs(gl[b] - logits).max() <= TOL
+            if all(margin(l) > 2 * TOL for l in logits):
+                assert gt[b].tolist() == toks
+    finally:
+        gm.close()
+
+
 def test_ignored_indices_are_reported(tiny):
     gm = tiny["gm"]
     V, torch = gm.V, gm.torch
