@@ -24,6 +24,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 N_ACTION = 7
 
+# HBM bytes per launch of the decode GEMMs at the c2 shape from hardware counters
+# (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain 256 MiB copy's reading:
+# factors 2.000 and 1.000; summary and commands in profiles/c2_gemm_traffic_pmc.md).
+# Measured once on the box, not live; keyed by epilogue of the <=32-row kernel.
+PMC_TRAFFIC_BYTES = {0: 101.1e6 + 0.1e6, 1: 65.0e6 + 1.1e6, 2: 180.7e6 + 0.04e6, 3: 262.7e6 + 0.1e6}
+
 KIND_NAMES = {0: "qkv_rope_scatter", 1: "proj_residual", 2: "gate_up_swiglu", 3: "head_logits"}
 CLASS_NAMES = {0: "rows<=32 (decode, head)", 1: "rows>32 (prefill)"}
 
@@ -51,7 +57,10 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2"])
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers than the model has")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-layers", type=int, default=3)
+    ap.add_argument("--cpu-layers", type=int, default=32)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain device copy of 256 MiB (a kernel of known traffic, "
+                         "the yardstick for hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path is single-GPU; streams would "
@@ -148,6 +157,13 @@ def main():
         ph = np.array([[e[k].elapsed_time(e[k + 1]) for k in range(3)] for e in evs])
         return wall, ph.mean(axis=0)
 
+    if args.calib_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)     # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # frame t-1: full prefill fills the cache and yields the statistics Alg. 1 needs
     full_prefill(d_eprev, attn_a)
     torch.cuda.synchronize()
@@ -175,13 +191,27 @@ def main():
                              "launches_per_step": n, "avg_us": tot / n * 1e3,
                              "ms_per_step": tot, "bytes": gemm_bytes(cfg, epi, rows)}
     V.vlac_profile_select(ctx, -1)
+    # an event bracket with nothing inside: what the two markers themselves add to a bracket
+    brackets = []
+    for _ in range(64):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        b.record()
+        brackets.append((a, b))
+    torch.cuda.synchronize()
+    ev_overhead_us = float(np.median([a.elapsed_time(b) for a, b in brackets])) * 1e3
     dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     kd = kernels[dom]
-    achieved = kd["bytes"] / (kd["avg_us"] * 1e-6) / 1e9
+    dur_us = max(kd["avg_us"] - ev_overhead_us, 1e-3)
+    achieved = kd["bytes"] / (dur_us * 1e-6) / 1e9
+    full_depth_c2 = (nl == 32 and dom < 4)
     roofline = {"bound": "hbm", "kernel": kd["name"], "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None, "bytes_per_launch": kd["bytes"],
-                "avg_launch_us": round(kd["avg_us"], 2), "launches_per_step": kd["launches_per_step"]}
+                "traffic": PMC_TRAFFIC_BYTES[dom % 4] if full_depth_c2 else None,
+                "bytes_per_launch": kd["bytes"], "avg_launch_us": round(dur_us, 2),
+                "avg_launch_us_raw_events": round(kd["avg_us"], 2),
+                "event_bracket_overhead_us": round(ev_overhead_us, 2),
+                "launches_per_step": kd["launches_per_step"]}
 
     weight_bytes = 2 * nl * (cfg.d_model * (cfg.q_dim + 2 * cfg.kv_dim) + cfg.q_dim * cfg.d_model +
                              3 * cfg.d_model * cfg.d_ffn)
@@ -238,6 +268,7 @@ def cpu_baseline(cfg, n_layers, prev, cur, e_prev, e_cur, patch, n_vis, top_k, s
     layers = {}
 
     def layer(l):
+        l %= 2      # two distinct weight sets, cycled over the depth: the arithmetic is the same
         if l not in layers:
             layers[l] = {k: v.float().numpy() for k, v in synth.make_layer(sub, seed, l).items()}
         return layers[l]
@@ -257,7 +288,8 @@ def cpu_baseline(cfg, n_layers, prev, cur, e_prev, e_cur, patch, n_vis, top_k, s
     return {"value": round(rows / prefill_s_full_depth, 2), "unit": "tokens/s", "cores": int(cores),
             "kind": "oracle",
             "sample": "fp64 numpy oracle: Alg. 1 on the frame pair (%.3f s) and the sparse prefill of "
-                      "%d rows through %d of %d layers (%.2f s, scaled x%.1f to full depth)"
+                      "%d rows through %d of %d layers (%.2f s, scaled x%.1f to full depth; two "
+                      "distinct random weight sets cycled over the depth)"
                       % (t1 - t0, rows, n_layers, cfg.n_layers, t2 - t1, cfg.n_layers / n_layers)}
 
 
