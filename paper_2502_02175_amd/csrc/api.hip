@@ -47,7 +47,7 @@ void free_all(vlac_ctx* c) {
     }
     free(c->layers);
   }
-  void* dev[] = {c->w_head, c->embed, c->g_final, c->rope_cos, c->rope_sin, c->h, c->xa, c->xf,
+  void* dev[] = {c->w_head, c->embed, c->g_final, c->rope_cos, c->rope_sin, c->h, c->hdec, c->xa, c->xf,
                  c->qbuf, c->partial, c->rpart, c->counters, c->rows, c->prev_slot, c->n_rows, c->slot_off, c->rank,
                  c->m_layer, c->n_rows_bl, c->statp, c->stat_counters, c->logits, c->tokens,
                  c->dec_rows, c->terms, c->flags, c->relevance, c->errword, c->scratch_i,
@@ -135,6 +135,7 @@ int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out) {
   A_(rope_cos, (size_t)ms * (m.head_dim / 2));
   A_(rope_sin, (size_t)ms * (m.head_dim / 2));
   A_(h, (size_t)mr * m.d_model);
+  A_(hdec, (size_t)2 * mb * m.d_model);
   A_(xa, frag_elems(mr, kpad_x));
   A_(xf, frag_elems(mr, ctx->kpad_f));
   A_(qbuf, frag_elems(mr, ctx->q_dim));
@@ -369,63 +370,122 @@ void run_layer(vlac_ctx* c, int layer, int B, int rows_cap, int rows_cap_per_str
   e.kv_layer_off = (size_t)layer * 2 * m.n_kv_heads * m.max_seq * m.head_dim;
   e.n_q_heads = m.n_q_heads; e.n_kv_heads = m.n_kv_heads; e.head_dim = m.head_dim;
   e.max_seq = m.max_seq;
-  e.h = c->h; e.d_model = m.d_model;
+  e.h = c->h; e.h_seq_stride = m.max_seq; e.d_model = m.d_model;
   e.rpart = c->rpart; e.rpart_rows = rows_cap;
   e.xf = c->xf; e.kc_f = c->kpad_f / 16; e.d_ffn = m.d_ffn;
   const int kc_d = c->kpad_d / 16;
 
-  // decode: the residual rows live in c->h and the RMSNorm is fused into the GEMM
-  const bool fuse = resid_in == c->h && *pending == 0 && gemm_can_fuse_norm(n_host, decode_pos, c->kpad_d);
-  if (fuse) {
-    launch_gemm(c, EPI_QKV, W.wqkv, c->qkv_dim / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st,
-                c->h, W.g_attn);
-  } else {
-    if (*pending)
-      launch_resid_norm_rows(c->f16, c->h, m.max_seq, c->rpart, *pending, rows_cap, c->h, m.max_seq,
-                             rows, prev_slot, n_rows, n_host, rows_cap, W.g_attn, m.rms_eps,
-                             m.d_model, c->xa, kc_d, st);
-    else
-      launch_rmsnorm_rows(c->f16, resid_in, resid_stride, rows, n_rows, n_host, decode_pos, rows_cap,
-                          W.g_attn, m.rms_eps, m.d_model, c->xa, kc_d, st);
-    launch_gemm(c, EPI_QKV, W.wqkv, c->qkv_dim / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st);
-  }
+  if (*pending)
+    launch_resid_norm_rows(c->f16, c->h, m.max_seq, c->rpart, *pending, rows_cap, c->h, m.max_seq,
+                           rows, prev_slot, n_rows, n_host, rows_cap, W.g_attn, m.rms_eps,
+                           m.d_model, c->xa, kc_d, st);
+  else
+    launch_rmsnorm_rows(c->f16, resid_in, resid_stride, rows, n_rows, n_host, decode_pos, rows_cap,
+                        W.g_attn, m.rms_eps, m.d_model, c->xa, kc_d, st);
+  launch_gemm(c, EPI_QKV, W.wqkv, c->qkv_dim / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st);
   *pending = 0;
   launch_attention(c, layer, B, rows_cap_per_stream, L_v, L_t, rows, slot_off, decode_pos, kv,
                    out_attn_mean, st);
   e.resid_src = resid_in; e.resid_seq_stride = resid_stride;
   const int s_o = launch_gemm(c, EPI_RESID, W.wo, m.d_model / 32, c->kpad_q, c->xa, n_rows, n_host,
                               rows_cap, e, st);
-  const bool split_o = rows_cap > 32 && s_o > 1;  // the few-rows kernel adds its splits up itself
-  if (fuse) {
-    launch_gemm(c, EPI_SWIGLU, W.wgu, 2 * m.d_ffn / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st,
-                c->h, W.g_ffn);
-  } else {
-    if (split_o)
-      launch_resid_norm_rows(c->f16, resid_in, resid_stride, c->rpart, s_o, rows_cap, c->h, m.max_seq,
-                             rows, nullptr, n_rows, n_host, rows_cap, W.g_ffn, m.rms_eps, m.d_model,
-                             c->xa, kc_d, st);
-    else
-      launch_rmsnorm_rows(c->f16, c->h, m.max_seq, rows, n_rows, n_host, decode_pos, rows_cap, W.g_ffn,
-                          m.rms_eps, m.d_model, c->xa, kc_d, st);
-    launch_gemm(c, EPI_SWIGLU, W.wgu, 2 * m.d_ffn / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st);
-  }
+  if (rows_cap > 32 && s_o > 1)  // the few-rows kernel adds its splits up itself
+    launch_resid_norm_rows(c->f16, resid_in, resid_stride, c->rpart, s_o, rows_cap, c->h, m.max_seq,
+                           rows, nullptr, n_rows, n_host, rows_cap, W.g_ffn, m.rms_eps, m.d_model,
+                           c->xa, kc_d, st);
+  else
+    launch_rmsnorm_rows(c->f16, c->h, m.max_seq, rows, n_rows, n_host, decode_pos, rows_cap, W.g_ffn,
+                        m.rms_eps, m.d_model, c->xa, kc_d, st);
+  launch_gemm(c, EPI_SWIGLU, W.wgu, 2 * m.d_ffn / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st);
   e.resid_src = c->h; e.resid_seq_stride = m.max_seq;
   const int s_d = launch_gemm(c, EPI_RESID, W.wdown, m.d_model / 32, c->kpad_f, c->xf, n_rows, n_host,
                               rows_cap, e, st);
   *pending = (rows_cap > 32 && s_d > 1) ? s_d : 0;
 }
 
-// Final norm + output head + greedy token for the B rows (stream b, position pos).
+// The residual rows of a decode pass with at most 4 streams: one row per stream in one
+// of the two row sets of c->hdec.  `pending` > 0: the rows are not complete yet, that
+// many split-K partial rows per stream (in c->rpart) have to be added first, which the
+// next fused norm does, storing the completed rows in the other set.
+struct DecodeResid {
+  int cur, pending;
+};
+
+NormIn decode_norm(vlac_ctx* c, int B, DecodeResid& r, const float* gain, bool keep) {
+  const int d = c->cfg.d_model;
+  NormIn n;
+  memset(&n, 0, sizeof(n));
+  n.src = c->hdec + (size_t)r.cur * c->cfg.max_batch * d;
+  n.src_stride = d;
+  n.gain = gain;
+  n.eps = c->cfg.rms_eps;
+  n.d = d;
+  if (r.pending) {
+    n.part = c->rpart; n.part_S = r.pending; n.part_rows = B;
+    if (keep) {
+      r.cur ^= 1;
+      n.dst = c->hdec + (size_t)r.cur * c->cfg.max_batch * d;
+      n.dst_stride = d;
+    }
+    r.pending = 0;
+  }
+  return n;
+}
+
+// One decoder layer of a decode pass over the rows (stream b, position pos), b < B <= 4:
+// every RMSNorm is fused into the GEMM that follows it, and the two projections with a
+// residual leave their split-K partial rows to the next norm (no hand-over inside them).
+void run_layer_decode(vlac_ctx* c, int layer, int B, int pos, bf16_t* kv, DecodeResid& r,
+                      hipStream_t st) {
+  const vlac_model_cfg& m = c->cfg;
+  const LayerW& W = c->layers[layer];
+  GemmEpi e;
+  memset(&e, 0, sizeof(e));
+  e.decode_pos = pos;
+  e.rope_cos = c->rope_cos; e.rope_sin = c->rope_sin;
+  e.qbuf = c->qbuf;
+  e.kv = kv;
+  e.kv_stream_stride = kv_elems_per_stream(m);
+  e.kv_layer_off = (size_t)layer * 2 * m.n_kv_heads * m.max_seq * m.head_dim;
+  e.n_q_heads = m.n_q_heads; e.n_kv_heads = m.n_kv_heads; e.head_dim = m.head_dim;
+  e.max_seq = m.max_seq;
+  e.d_model = m.d_model;
+  e.h_compact = 1; e.h_seq_stride = 1; e.resid_seq_stride = 1;
+  e.rpart = c->rpart; e.rpart_rows = B; e.defer_split = 1;
+  e.xf = c->xf; e.kc_f = c->kpad_f / 16; e.d_ffn = m.d_ffn;
+
+  NormIn n = decode_norm(c, B, r, W.g_attn, true);
+  launch_gemm(c, EPI_QKV, W.wqkv, c->qkv_dim / 32, c->kpad_d, c->xa, nullptr, B, B, e, st, &n);
+  launch_attention(c, layer, B, 1, 0, 0, nullptr, nullptr, pos, kv, nullptr, st);
+  float* hrow = c->hdec + (size_t)r.cur * m.max_batch * m.d_model;
+  e.resid_src = hrow; e.h = hrow;
+  const int s_o = launch_gemm(c, EPI_RESID, W.wo, m.d_model / 32, c->kpad_q, c->xa, nullptr, B, B, e, st);
+  r.pending = s_o > 1 ? s_o : 0;
+  n = decode_norm(c, B, r, W.g_ffn, true);
+  launch_gemm(c, EPI_SWIGLU, W.wgu, 2 * m.d_ffn / 32, c->kpad_d, c->xa, nullptr, B, B, e, st, &n);
+  hrow = c->hdec + (size_t)r.cur * m.max_batch * m.d_model;
+  e.resid_src = hrow; e.h = hrow;
+  const int s_d = launch_gemm(c, EPI_RESID, W.wdown, m.d_model / 32, c->kpad_f, c->xf, nullptr, B, B, e, st);
+  r.pending = s_d > 1 ? s_d : 0;
+}
+
+// Final norm + output head + greedy token for B rows: (stream b, position pos) of the
+// residual stream, or, with `fused` given, the rows of a decode pass (norm fused).
 void run_head(vlac_ctx* c, int B, int pos, float* logits, size_t logits_stride, int32_t* out_token,
-              int out_stride, int32_t* token_copy, hipStream_t st) {
+              int out_stride, int32_t* token_copy, hipStream_t st, const NormIn* fused = nullptr) {
   const vlac_model_cfg& m = c->cfg;
   GemmEpi e;
   memset(&e, 0, sizeof(e));
   e.decode_pos = pos;
   e.logits = logits; e.vocab = m.vocab; e.logits_stride = logits_stride;
-  if (gemm_can_fuse_norm(B, pos, c->kpad_d)) {
-    launch_gemm(c, EPI_LOGITS, c->w_head, m.vocab / 32, c->kpad_d, c->xa, nullptr, B, B, e, st, c->h,
-                c->g_final);
+  if (fused) {
+    launch_gemm(c, EPI_LOGITS, c->w_head, m.vocab / 32, c->kpad_d, c->xa, nullptr, B, B, e, st, fused);
+  } else if (gemm_can_fuse_norm(B, pos, c->kpad_d)) {
+    NormIn n;
+    memset(&n, 0, sizeof(n));
+    n.src = c->h + (size_t)pos * m.d_model; n.src_stride = (size_t)m.max_seq * m.d_model;
+    n.gain = c->g_final; n.eps = m.rms_eps; n.d = m.d_model;
+    launch_gemm(c, EPI_LOGITS, c->w_head, m.vocab / 32, c->kpad_d, c->xa, nullptr, B, B, e, st, &n);
   } else {
     launch_rmsnorm_rows(c->f16, c->h, m.max_seq, nullptr, nullptr, B, pos, B, c->g_final, m.rms_eps,
                         m.d_model, c->xa, c->kpad_d / 16, st);
@@ -504,16 +564,27 @@ int vlac_decode_action(vlac_ctx* ctx, int B, int L, int n_new, const int32_t* fi
   if (n_new == 0) return VLAC_OK;
   hipStream_t st = (hipStream_t)stream;
   const int ms = m.max_seq;
+  const bool fused = gemm_can_fuse_norm(B, L, ctx->kpad_d) && ctx->rpart_floats >= (size_t)8 * B * m.d_model;
   for (int t = 0; t < n_new; ++t) {
-    launch_embed_rows(ctx->embed, t == 0 ? first_token : ctx->tokens, B, m.d_model, m.vocab, ctx->h,
-                      ms, L + t, st);
-    int pending = 0;  // at most 32 rows: the few-rows kernel never leaves partial rows behind
-    for (int l = 0; l < m.n_layers; ++l)
-      run_layer(ctx, l, B, B, 1, 0, 0, ctx->h, ms, nullptr, nullptr, B, L + t, nullptr, nullptr,
-                (bf16_t*)kv_cache, nullptr, &pending, st);
-    run_head(ctx, B, L + t, out_logits ? out_logits + (size_t)t * m.vocab : ctx->logits,
-             out_logits ? (size_t)n_new * m.vocab : (size_t)m.vocab, out_tokens + t, n_new,
-             ctx->tokens, st);
+    const int32_t* tok = t == 0 ? first_token : ctx->tokens;
+    float* logits = out_logits ? out_logits + (size_t)t * m.vocab : ctx->logits;
+    const size_t lstride = out_logits ? (size_t)n_new * m.vocab : (size_t)m.vocab;
+    if (fused) {
+      // rows (b, 0) of a [max_batch, 1, d] plane: the first residual row set
+      launch_embed_rows(ctx->embed, tok, B, m.d_model, m.vocab, ctx->hdec, 1, 0, st);
+      DecodeResid r = {0, 0};
+      for (int l = 0; l < m.n_layers; ++l)
+        run_layer_decode(ctx, l, B, L + t, (bf16_t*)kv_cache, r, st);
+      const NormIn n = decode_norm(ctx, B, r, ctx->g_final, false);
+      run_head(ctx, B, L + t, logits, lstride, out_tokens + t, n_new, ctx->tokens, st, &n);
+    } else {
+      launch_embed_rows(ctx->embed, tok, B, m.d_model, m.vocab, ctx->h, ms, L + t, st);
+      int pending = 0;  // at most 32 rows: the few-rows kernel adds its splits up itself
+      for (int l = 0; l < m.n_layers; ++l)
+        run_layer(ctx, l, B, B, 1, 0, 0, ctx->h, ms, nullptr, nullptr, B, L + t, nullptr, nullptr,
+                  (bf16_t*)kv_cache, nullptr, &pending, st);
+      run_head(ctx, B, L + t, logits, lstride, out_tokens + t, n_new, ctx->tokens, st);
+    }
   }
   VLAC_HIP(hipGetLastError());
   return VLAC_OK;

@@ -102,6 +102,7 @@ struct vlac_ctx {
   float *rope_cos, *rope_sin;  // [max_seq, hd/2]
   // workspace (device)
   float* h;         // residual stream [max_batch, max_seq, d]
+  float* hdec;      // decode with the fused norm: two residual row sets [2][max_batch, d]
   bf16_t* xa;       // normed rows / attention output, fragment order
   bf16_t* xf;       // SwiGLU output, fragment order
   bf16_t* qbuf;     // rotated queries, fragment order per head
@@ -194,22 +195,39 @@ struct GemmEpi {
   bf16_t* kv;             // cache base of layer 0, stream 0
   size_t kv_stream_stride, kv_layer_off;
   int n_q_heads, n_kv_heads, head_dim, max_seq;
-  // EPI_RESID
+  // EPI_RESID: h[b][pos] = resid_src[b][pos] + projection; rows of h_seq_stride /
+  // resid_seq_stride positions per stream (h_compact: one row per stream, pos is ignored)
   const float* resid_src; int resid_seq_stride;
-  float* h; int d_model;
+  float* h; int h_seq_stride; int h_compact; int d_model;
   float* rpart; int rpart_rows;  // split-K partial rows [split][rpart_rows][d_model]
+  int defer_split;  // few-rows kernel with S > 1: leave the partial rows in rpart
   // EPI_SWIGLU
   bf16_t* xf; int kc_f; int d_ffn;
   // EPI_LOGITS
   float* logits; int vocab; size_t logits_stride;  // elements between rows
 };
+// RMSNorm fused into the few-rows GEMM: x = src row (+ split-K partial rows, in split
+// order), operand = x * rsqrt(mean(x^2) + eps) * gain
+struct NormIn {
+  const float* src;    // row 0 of the fp32 source rows
+  size_t src_stride;   // floats between consecutive rows
+  const float* gain;
+  float eps;
+  int d;
+  const float* part;   // partial rows [part_S][part_rows][d] still to be added, or null
+  int part_S, part_rows;
+  float* dst;          // where the completed rows are stored (never src), or null
+  size_t dst_stride;
+};
 int gemm_init();  // one-time kernel attribute setup; returns hipError_t
 // returns the split-K factor used; for EPI_RESID a factor S > 1 means that the result is
-// NOT in the residual stream yet but in e.rpart as S partial rows (launch_resid_norm_rows)
+// NOT in the residual stream yet but in e.rpart as S partial rows (more than 32 rows:
+// always; at most 32 rows: if e.defer_split is set) for the consumer to add up
+// (launch_resid_norm_rows, or NormIn::part of the next projection)
 int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, const bf16_t* xp,
                  const int* n_rows, int n_rows_host, int rows_cap, const GemmEpi& e, hipStream_t st,
-                 const float* norm_src = nullptr, const float* norm_gain = nullptr);
-// true if launch_gemm may be given norm_src / norm_gain (RMSNorm fused into the GEMM)
+                 const NormIn* norm = nullptr);
+// true if launch_gemm may be given a NormIn (RMSNorm fused into the GEMM)
 bool gemm_can_fuse_norm(int n_rows_host, int decode_pos, int kpad);
 
 // attn.hip

@@ -28,18 +28,14 @@
 //    is sized for the worst case and surplus workgroups leave at once.
 //  * Workgroup ids are dealt round-robin to the 8 XCDs; row blocks of one weight
 //    tile are mapped to the same XCD so that they share its L2.
+#include <cstring>
 #include "common.h"
 
 struct GemmArgs {
   const uint4* wp;    // weights, fragment order, 64 uint4 per tile
   const uint4* xp;    // activations, fragment order
   const uint4* zero_tile;  // 1 KiB of zeros
-  // fused RMSNorm of the input rows (few-rows kernel only): fp32 source rows
-  // [stream, norm_seq_stride, norm_d] at position e.decode_pos, gain, epsilon
-  const float* norm_src;
-  const float* norm_gain;
-  float norm_eps;
-  int norm_d, norm_seq_stride;
+  NormIn norm;        // fused RMSNorm of the input rows (few-rows kernel only)
   int NB;             // weight row blocks (32 output features each)
   int KS;             // K steps (64 k = 4 tiles each)
   const int* n_rows;  // device: rows in use
@@ -107,8 +103,9 @@ __device__ inline void epilogue_tile(const GemmEpi& e, int nb, int slot, int id,
         for (int k = 0; k < 4; ++k) dst[(8 * q4 + 4 * g + k) * 8] = f2op<F16>(acc[4 * q4 + k]);
     }
   } else if constexpr (EPI == EPI_RESID) {
-    const float* rs = e.resid_src + ((size_t)b * e.resid_seq_stride + pos) * e.d_model + nb * 32 + 4 * g;
-    float* hp = e.h + ((size_t)b * e.max_seq + pos) * e.d_model + nb * 32 + 4 * g;
+    const int hpos = e.h_compact ? 0 : pos;
+    const float* rs = e.resid_src + ((size_t)b * e.resid_seq_stride + hpos) * e.d_model + nb * 32 + 4 * g;
+    float* hp = e.h + ((size_t)b * e.h_seq_stride + hpos) * e.d_model + nb * 32 + 4 * g;
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
       float4 r = *(const float4*)(rs + 8 * q4);
@@ -336,14 +333,22 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(GemmArgs a) {
 // the matching activation tiles straight from L2 (only the lanes of real rows
 // load anything).  With S > 1 the K range is also split over S workgroups
 // (N = d_model gives only d/32 blocks); the partial tiles are 4 KiB each.
-// NORM: for up to 4 rows the RMSNorm of the input rows is done here as well (every
-// workgroup normalises the rows itself, from L2, while its first weight tiles are
-// in flight), which saves a launch per GEMM in the decode loop.
+// Where the input is the residual stream and there are at most 4 rows, its RMSNorm is
+// done here as well: every workgroup normalises the rows itself (from L2, while its first
+// weight tiles are in flight) and keeps the operand slices of its K range in LDS, which
+// saves a launch per GEMM in the decode loop.  Split-K partial rows that the previous
+// projection left behind are added to the rows on the way (in a fixed order, the same in
+// every workgroup), and workgroup 0 stores the completed rows for the next projection.
 // ---------------------------------------------------------------------------
-template <int EPI, bool F16, bool NORM>
+// XMODE: where the row operand comes from.
+//   X_GLOBAL  every lane loads its 16 bytes of the 32-row operand tile from L2 (any row count)
+//   X_NORM4/8 RMSNorm of fp32 rows of at most 4096 / 8192 elements, slices [k/8][row] in LDS
+enum { X_GLOBAL = 0, X_NORM4 = 1, X_NORM8 = 2 };
+
+template <int EPI, bool F16, int XMODE>
 __global__ __launch_bounds__(256) void gemm_few_kernel(GemmArgs a) {
   __shared__ float red[3][16][64];
-  extern __shared__ uint4 xlds[];  // NORM: the normalised rows as operand slices [k/8][row]
+  extern __shared__ uint4 xlds[];  // operand slices [k/8 - lo8][row]
   constexpr int U = 8;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int nb = blockIdx.x / a.S, s = blockIdx.x - nb * a.S;
@@ -354,6 +359,7 @@ __global__ __launch_bounds__(256) void gemm_few_kernel(GemmArgs a) {
   const int perw = (max(c_hi - c_lo, 0) + 3) / 4, w_lo = c_lo + w * perw, w_hi = min(c_hi, w_lo + perw);
   const uint4* wsrc = a.wp + (size_t)nb * KC * 64 + lane;
   const uint4* xsrc = a.xp + lane;
+  const int lo8 = 2 * c_lo, n8 = 2 * max(c_hi - c_lo, 0);  // this workgroup's k/8 range
 
   f32x16 acc;
 #pragma unroll
@@ -368,61 +374,120 @@ __global__ __launch_bounds__(256) void gemm_few_kernel(GemmArgs a) {
     for (int u = 0; u < U; ++u) {
       const int cc = max(min(c + u, w_hi - 1), 0);
       b[u] = wsrc[(size_t)cc * 64];
-      if constexpr (!NORM) {
+      if constexpr (XMODE == X_GLOBAL) {
         const uint4* xs = (c + u < w_hi) ? xsrc + (size_t)cc * 64 : a.zero_tile + lane;
         x[u] = *xs;
       }
     }
   };
   auto compute = [&](int c, uint4(&b)[U], uint4(&x)[U]) {
-    if constexpr (NORM) {  // the operand slices come from LDS: [k/8][row], rows < n_rows only
+    if constexpr (XMODE != X_GLOBAL) {
       const int j = lane & 31, g = lane >> 5;
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int cc = max(min(c + u, w_hi - 1), 0);
-        x[u] = (j < n_rows && c + u < w_hi) ? xlds[(cc * 2 + g) * n_rows + j] : make_uint4(0, 0, 0, 0);
+        x[u] = (j < n_rows && c + u < w_hi) ? xlds[(cc * 2 + g - lo8) * n_rows + j]
+                                            : make_uint4(0, 0, 0, 0);
       }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) acc = mfma32<F16>(b[u], x[u], acc);
   };
-  // the first two batches of weight tiles fly while the rows are normalised
+
+  // Loads return in issue order: row 0, the gains and the first two splits of its partial
+  // rows are requested BEFORE the first two batches of weight tiles, which then fly while
+  // the row is normalised.
+  constexpr int MAXI = XMODE == X_NORM8 ? 8 : 4;  // 4 values per thread and 1024 of the row
+  [[maybe_unused]] float4 v[MAXI], gn[MAXI], t0[MAXI], t1[MAXI];
+  if constexpr (XMODE != X_GLOBAL) {
+    const NormIn& nm = a.norm;
+    const size_t pstride = (size_t)nm.part_rows * nm.d;
+#pragma unroll
+    for (int i = 0; i < MAXI; ++i) {
+      const int k = tid * 4 + i * 1024;
+      v[i] = gn[i] = t0[i] = t1[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (k < nm.d) {
+        v[i] = *(const float4*)(nm.src + k);
+        gn[i] = *(const float4*)(nm.gain + k);
+        if (nm.part_S > 0) t0[i] = *(const float4*)(nm.part + k);
+        if (nm.part_S > 1) t1[i] = *(const float4*)(nm.part + pstride + k);
+      }
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
   load(w_lo, bw[0], ax[0]);
   load(w_lo + U, bw[1], ax[1]);
   __builtin_amdgcn_sched_barrier(0);
 
-  if constexpr (NORM) {
-    // RMSNorm of the (few) rows, fused: x * rsqrt(mean(x^2) + eps) * g, one wave per row
-    const int d = a.norm_d;
-    for (int j = w; j < n_rows; j += 4) {
-      const float* x = a.norm_src + ((size_t)j * a.norm_seq_stride + a.e.decode_pos) * d;
-      float ss = 0.f;
-      for (int k = lane * 4; k < d; k += 256) {
-        const float4 v = *(const float4*)(x + k);
-        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  if constexpr (XMODE != X_GLOBAL) {
+    // RMSNorm of the rows: x * rsqrt(mean(x^2) + eps) * g, with x = source row + partial
+    // rows in split order.  One pass over each row: every thread keeps its values in
+    // registers, the sum of squares goes through LDS.
+    const NormIn& nm = a.norm;
+    const int d = nm.d;
+    const size_t pstride = (size_t)nm.part_rows * d;
+    auto add4 = [](float4& x, const float4& y) { x.x += y.x; x.y += y.y; x.z += y.z; x.w += y.w; };
+    auto finish_row = [&](int j) {
+#pragma unroll
+      for (int i = 0; i < MAXI; ++i) {
+        add4(v[i], t0[i]);
+        add4(v[i], t1[i]);
       }
-      for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-      const float r = rsqrtf(ss / (float)d + a.norm_eps);
-      for (int k8 = lane; k8 < KC * 2; k8 += 64) {
-        uint4 o = make_uint4(0, 0, 0, 0);
-        if (k8 * 8 < d) {
-          const float4 v0 = *(const float4*)(x + k8 * 8), v1 = *(const float4*)(x + k8 * 8 + 4);
-          const float4 g0 = *(const float4*)(a.norm_gain + k8 * 8);
-          const float4 g1 = *(const float4*)(a.norm_gain + k8 * 8 + 4);
-          o.x = pack_op2<F16>(v0.x * r * g0.x, v0.y * r * g0.y);
-          o.y = pack_op2<F16>(v0.z * r * g0.z, v0.w * r * g0.w);
-          o.z = pack_op2<F16>(v1.x * r * g1.x, v1.y * r * g1.y);
-          o.w = pack_op2<F16>(v1.z * r * g1.z, v1.w * r * g1.w);
+      for (int ss = 2; ss < nm.part_S; ++ss) {
+#pragma unroll
+        for (int i = 0; i < MAXI; ++i) {
+          const int k = tid * 4 + i * 1024;
+          if (k < d) add4(v[i], *(const float4*)(nm.part + ss * pstride + (size_t)j * d + k));
         }
-        xlds[k8 * n_rows + j] = o;
       }
+      if (nm.dst && blockIdx.x == 0) {
+#pragma unroll
+        for (int i = 0; i < MAXI; ++i) {
+          const int k = tid * 4 + i * 1024;
+          if (k < d) *(float4*)(nm.dst + (size_t)j * nm.dst_stride + k) = v[i];
+        }
+      }
+      float ss = 0.f;
+#pragma unroll
+      for (int i = 0; i < MAXI; ++i)
+        ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+      for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+      __syncthreads();  // red is free again
+      if (lane == 0) red[0][0][w] = ss;
+      __syncthreads();
+      const float r =
+          rsqrtf((red[0][0][0] + red[0][0][1] + red[0][0][2] + red[0][0][3]) / (float)d + nm.eps);
+#pragma unroll
+      for (int i = 0; i < MAXI; ++i) {
+        const int k = tid * 4 + i * 1024, k8 = k >> 3;
+        if (k8 >= lo8 && k8 < lo8 + n8) {  // k >= d: zeros (K padding)
+          uint2* dst = (uint2*)&xlds[(k8 - lo8) * n_rows + j];
+          dst[(k >> 2) & 1] = make_uint2(pack_op2<F16>(v[i].x * r * gn[i].x, v[i].y * r * gn[i].y),
+                                         pack_op2<F16>(v[i].z * r * gn[i].z, v[i].w * r * gn[i].w));
+        }
+      }
+    };
+    // row 0 apart from the loop: its loads are older than the weight tiles, and code
+    // shared with the later rows would wait for those as well
+    finish_row(0);
+    for (int j = 1; j < n_rows; ++j) {
+#pragma unroll
+      for (int i = 0; i < MAXI; ++i) {
+        const int k = tid * 4 + i * 1024;
+        if (k < d) {
+          v[i] = *(const float4*)(nm.src + (size_t)j * nm.src_stride + k);
+          if (nm.part_S > 0) t0[i] = *(const float4*)(nm.part + (size_t)j * d + k);
+          if (nm.part_S > 1) t1[i] = *(const float4*)(nm.part + pstride + (size_t)j * d + k);
+        }
+      }
+      finish_row(j);
     }
     __syncthreads();
   }
 
-  // Loads return in issue order, so the batch a compute phase needs must have been
-  // issued BEFORE the batch that flies behind it; the fences stop the instruction
-  // scheduler from mixing the phases (which would drain the queue every iteration).
+  // The batch a compute phase needs must have been issued BEFORE the batch that flies
+  // behind it; the fences stop the instruction scheduler from mixing the phases (which
+  // would drain the queue every iteration).
   for (int c = w_lo; c < w_hi; c += 2 * U) {
     compute(c, bw[0], ax[0]);
     __builtin_amdgcn_sched_barrier(0);
@@ -443,6 +508,19 @@ __global__ __launch_bounds__(256) void gemm_few_kernel(GemmArgs a) {
 #pragma unroll
   for (int i = 0; i < 16; ++i) acc[i] += red[0][i][lane] + red[1][i][lane] + red[2][i][lane];
 
+  if (EPI == EPI_RESID && a.S > 1 && a.e.defer_split) {
+    // the split's partial rows [split][row][feature] are left for the consumer (the
+    // fused norm of the next projection) to add up: nothing is handed over in here
+    const int slot = lane & 31, g = lane >> 5;
+    if (slot < n_rows) {
+      float* dst = a.e.rpart + ((size_t)s * a.e.rpart_rows + slot) * a.e.d_model + nb * 32 + 4 * g;
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4)
+        *(float4*)(dst + 8 * q4) =
+            make_float4(acc[4 * q4], acc[4 * q4 + 1], acc[4 * q4 + 2], acc[4 * q4 + 3]);
+    }
+    return;
+  }
   if (a.S > 1) {  // wave 0 alone hands over / collects the partial tile
     float* base = a.partial + (size_t)nb * a.S * 1024;
 #pragma unroll
@@ -514,32 +592,35 @@ static void launch_mt(int epi, const GemmArgs& a, int grid, hipStream_t st) {
   }
 }
 
-template <bool F16, bool NORM>
+template <bool F16, int XMODE>
 static void launch_few(int epi, const GemmArgs& a, int grid, size_t shm, hipStream_t st) {
   switch (epi) {
     case EPI_QKV:
-      hipLaunchKernelGGL((gemm_few_kernel<EPI_QKV, F16, NORM>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_QKV, F16, XMODE>), dim3(grid), dim3(256), shm, st, a);
       break;
     case EPI_RESID:
-      hipLaunchKernelGGL((gemm_few_kernel<EPI_RESID, F16, NORM>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_RESID, F16, XMODE>), dim3(grid), dim3(256), shm, st, a);
       break;
     case EPI_SWIGLU:
-      hipLaunchKernelGGL((gemm_few_kernel<EPI_SWIGLU, F16, NORM>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_SWIGLU, F16, XMODE>), dim3(grid), dim3(256), shm, st, a);
       break;
     default:
-      hipLaunchKernelGGL((gemm_few_kernel<EPI_LOGITS, F16, NORM>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_LOGITS, F16, XMODE>), dim3(grid), dim3(256), shm, st, a);
       break;
   }
 }
 
+// LDS budget of the normalised rows (on top of 12 KiB of static LDS)
+static const size_t kStageBytes = 49152;
+
 bool gemm_can_fuse_norm(int n_rows_host, int decode_pos, int kpad) {
-  return n_rows_host >= 1 && n_rows_host <= 4 && decode_pos >= 0 &&
-         (size_t)(kpad / 8) * n_rows_host * 16 <= 40960;
+  return n_rows_host >= 1 && n_rows_host <= 4 && decode_pos >= 0 && kpad <= 8192 &&
+         (size_t)(kpad / 8) * n_rows_host * 16 <= kStageBytes;
 }
 
 int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, const bf16_t* xp,
                  const int* n_rows, int n_rows_host, int rows_cap, const GemmEpi& e, hipStream_t st,
-                 const float* norm_src, const float* norm_gain) {
+                 const NormIn* norm) {
   GemmArgs a;
   a.wp = (const uint4*)wp;
   a.xp = (const uint4*)xp;
@@ -548,11 +629,8 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, 
   a.KS = kpad / 64;
   a.n_rows = n_rows;
   a.n_rows_val = n_rows_host;
-  a.norm_src = norm_src;
-  a.norm_gain = norm_gain;
-  a.norm_eps = c->cfg.rms_eps;
-  a.norm_d = c->cfg.d_model;
-  a.norm_seq_stride = c->cfg.max_seq;
+  memset(&a.norm, 0, sizeof(a.norm));
+  if (norm) a.norm = *norm;
   a.partial = c->partial;
   a.counters = c->counters;
   a.e = e;
@@ -570,13 +648,19 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, 
     a.S = S;
     a.MB = 1;
     a.P = n_blocks * S;
-    if (norm_src) {  // only offered when gemm_can_fuse_norm() holds
-      const size_t shm = (size_t)(kpad / 8) * n_rows_host * 16;
-      if (c->f16) launch_few<true, true>(epi, a, a.P, shm, st);
-      else launch_few<false, true>(epi, a, a.P, shm, st);
+    if (norm) {  // only offered when gemm_can_fuse_norm() holds
+      // LDS for the normalised rows: this workgroup's share of K, [k/8][row] 16-byte slices
+      const size_t shm = (size_t)(2 * ((KC + S - 1) / S)) * n_rows_host * 16;
+      if (norm->d <= 4096) {
+        if (c->f16) launch_few<true, X_NORM4>(epi, a, a.P, shm, st);
+        else launch_few<false, X_NORM4>(epi, a, a.P, shm, st);
+      } else {
+        if (c->f16) launch_few<true, X_NORM8>(epi, a, a.P, shm, st);
+        else launch_few<false, X_NORM8>(epi, a, a.P, shm, st);
+      }
     } else {
-      if (c->f16) launch_few<true, false>(epi, a, a.P, 0, st);
-      else launch_few<false, false>(epi, a, a.P, 0, st);
+      if (c->f16) launch_few<true, X_GLOBAL>(epi, a, a.P, 0, st);
+      else launch_few<false, X_GLOBAL>(epi, a, a.P, 0, st);
     }
   } else {
     constexpr int MT = 4;
