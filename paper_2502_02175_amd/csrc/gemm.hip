@@ -137,7 +137,7 @@ __device__ inline void epilogue_tile(const GemmEpi& e, int nb, int slot, int id,
 // and the compiler can count the loads in flight exactly).
 template <int NA, int MT, int EPI, bool F16>
 __device__ __forceinline__ void rows_body(const GemmArgs& a, uint4* lds, int* s_last, int tile,
-                                          int s, int mb, int n_rows) {
+                                          int s, int mb, int n_rows, uint32_t pf0, uint32_t pf1) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int row0 = mb * MT * 32;
   const int nb = tile * 4 + w;
@@ -212,6 +212,7 @@ __device__ __forceinline__ void rows_body(const GemmArgs& a, uint4* lds, int* s_
   VLAC_LOAD_A(2, A2) VLAC_LOAD_B(2, B2)
   VLAC_LOAD_A(3, A3) VLAC_LOAD_B(3, B3)
   __builtin_amdgcn_sched_barrier(0);
+  asm volatile("" ::"v"(pf0), "v"(pf1));  // the touch loads end here, behind the real ones
   VLAC_STORE_A(0, A0)
   // Whole groups of 4 steps run in a loop without any branch inside (a conditional step
   // would make the compiler assume the shortest path around the loop and wait for almost
@@ -308,20 +309,50 @@ template <int MT, int EPI, bool F16>
 __global__ __launch_bounds__(256) void gemm_rows_kernel(GemmArgs a) {
   extern __shared__ uint4 lds[];  // [2][MT][256]: two stages of MT activation tiles x 4 k-tiles
   __shared__ int s_last;
-  // workgroup id -> (weight tile, split, row block); id % 8 is the XCD
-  const int x = blockIdx.x, y = x >> 3;
-  const int mb = y % a.MB, p = (y / a.MB) * 8 + (x & 7);
+  // workgroup id -> (row block, weight tile, split); id % 8 is the XCD.  With the row
+  // count known on the host every row block has work, and the blocks of one weight tile
+  // sit next to each other.  Otherwise the grid covers the largest possible row count,
+  // and the row block is the slowest index: the workgroups of empty row blocks (which
+  // only find that out from device memory) would else sit between the working ones in
+  // dispatch order and hold their places.  (Measured: that pays when one row block's
+  // workgroups fit on the chip at once, P <= 256; with more, the staggered start of the
+  // interleaved order is the better one.)
+  int mb, p;
+  if (a.n_rows_val >= 0 || a.P > 256) {
+    const int y = blockIdx.x >> 3;
+    mb = y % a.MB;
+    p = (y / a.MB) * 8 + (blockIdx.x & 7);
+  } else {
+    const int p8 = (a.P + 7) & ~7;
+    mb = blockIdx.x / p8;
+    p = blockIdx.x - mb * p8;
+  }
   if (p >= a.P) return;
   const int tile = p / a.S, s = p - tile * a.S;
+  // The row count sits in device memory, and nothing can be loaded into registers before
+  // it is known (the loop is specialised by it).  The first row block, which always has
+  // work, touches the first 16 KiB of every wave's weight stream meanwhile (one dword per
+  // 128-byte line), so that the stream starts from L2 one round trip later.
+  uint32_t pf0 = 0, pf1 = 0;
+  if (mb == 0 && a.n_rows_val < 0) {
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, nb = min(tile * 4 + w, a.NB - 1);
+    const int q = a.KS / a.S, r = a.KS % a.S;
+    const int ks0 = s * q + min(s, r), n_ks = q + (s < r ? 1 : 0);
+    if (n_ks >= 4) {
+      const uint32_t* pw = (const uint32_t*)(a.wp + ((size_t)nb * 4 * a.KS + 4 * ks0) * 64) + lane * 32;
+      pf0 = pw[0];
+      pf1 = pw[2048];
+    }
+  }
   const int n_rows = a.n_rows_val >= 0 ? a.n_rows_val : *a.n_rows;
   const int row0 = mb * MT * 32;
   if (row0 >= n_rows) return;
   static_assert(MT == 4, "row blocks are 4 tiles of 32 rows");
   switch (min(MT, (n_rows - row0 + 31) >> 5)) {
-    case 1: rows_body<1, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows); break;
-    case 2: rows_body<2, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows); break;
-    case 3: rows_body<3, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows); break;
-    default: rows_body<4, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows); break;
+    case 1: rows_body<1, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows, pf0, pf1); break;
+    case 2: rows_body<2, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows, pf0, pf1); break;
+    case 3: rows_body<3, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows, pf0, pf1); break;
+    default: rows_body<4, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows, pf0, pf1); break;
   }
 }
 

@@ -215,12 +215,80 @@ void launch_rmsnorm_rows(bool f16, const float* src, int seq_stride, const int* 
 }
 
 // Residual add with the split-K partial rows of the projection that came before, then
-// (optionally) the RMSNorm that comes next: h[row] = resid[row] + sum_s part[s][slot];
-// xp[slot] = RMSNorm(h[row]) * gain.  One workgroup per row (S + 1 independent 16-byte
-// loads per thread and pass keep the memory system busy; the work per row is all
-// latency); a thread re-reads only what it wrote itself.  gain == nullptr: no norm.
-template <bool F16>
+// (optionally) the RMSNorm that comes next: h[row] = resid[row] + sum_s part[s][slot]
+// (in split order); xp[slot] = RMSNorm(h[row]) * gain.  One workgroup per row; the row
+// stays in registers (MAXI float4 per thread, d <= 1024 * MAXI), and all of a thread's
+// loads of the row and of two splits are in flight together: the work per row is all
+// latency.  gain == nullptr: no norm.
+template <bool F16, int MAXI>
 __global__ __launch_bounds__(256) void resid_norm_rows_kernel(
+    const float* __restrict__ resid, int resid_seq_stride, const float* __restrict__ part, int S,
+    int part_rows, float* __restrict__ h, int h_seq_stride, const int* __restrict__ rows,
+    const int* __restrict__ part_slot, const int* __restrict__ n_rows, int n_rows_host,
+    const float* __restrict__ gain, float eps, int d, bf16_t* __restrict__ xp, int KC) {
+  __shared__ float red[4];
+  const int slot = blockIdx.x, tid = threadIdx.x;
+  if (slot >= (n_rows_host >= 0 ? n_rows_host : *n_rows)) return;
+  const int id = rows[slot];
+  // the partial rows are indexed by the slot the row had when the GEMM ran
+  const int pslot = part_slot ? part_slot[slot] : slot;
+  const float* r = resid + ((size_t)(id >> 16) * resid_seq_stride + (id & 0xffff)) * d;
+  float* y = h + ((size_t)(id >> 16) * h_seq_stride + (id & 0xffff)) * d;
+  const float* p0 = part + (size_t)pslot * d;
+  const size_t pstride = (size_t)part_rows * d;
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 v[MAXI], g[MAXI], t0[MAXI], t1[MAXI];
+#pragma unroll
+  for (int i = 0; i < MAXI; ++i) {
+    const int k = tid * 4 + i * 1024;
+    v[i] = g[i] = zero;
+    if (k < d) {
+      v[i] = *(const float4*)(r + k);
+      if (gain) g[i] = *(const float4*)(gain + k);
+    }
+  }
+  for (int s = 0; s < S; s += 2) {  // fixed order
+#pragma unroll
+    for (int i = 0; i < MAXI; ++i) {
+      const int k = tid * 4 + i * 1024;
+      t0[i] = t1[i] = zero;
+      if (k < d) {
+        t0[i] = *(const float4*)(p0 + (size_t)s * pstride + k);
+        if (s + 1 < S) t1[i] = *(const float4*)(p0 + (size_t)(s + 1) * pstride + k);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < MAXI; ++i) {
+      v[i].x += t0[i].x; v[i].y += t0[i].y; v[i].z += t0[i].z; v[i].w += t0[i].w;
+      v[i].x += t1[i].x; v[i].y += t1[i].y; v[i].z += t1[i].z; v[i].w += t1[i].w;
+    }
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXI; ++i) {
+    const int k = tid * 4 + i * 1024;
+    if (k < d) *(float4*)(y + k) = v[i];
+    ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+  }
+  if (!gain) return;
+  ss = wave_sum(ss);
+  if ((tid & 63) == 0) red[tid >> 6] = ss;
+  __syncthreads();
+  const float rinv = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
+#pragma unroll
+  for (int i = 0; i < MAXI; ++i) {
+    const int k = tid * 4 + i * 1024;
+    if (k < d)
+      *(uint2*)(xp + frag_off(slot, k, KC)) =
+          make_uint2(pack_op2<F16>(v[i].x * rinv * g[i].x, v[i].y * rinv * g[i].y),
+                     pack_op2<F16>(v[i].z * rinv * g[i].z, v[i].w * rinv * g[i].w));
+  }
+}
+
+// Rows longer than 8192: the row is re-read instead of kept (a thread re-reads only what
+// it wrote itself).
+template <bool F16>
+__global__ __launch_bounds__(256) void resid_norm_rows_long_kernel(
     const float* __restrict__ resid, int resid_seq_stride, const float* __restrict__ part, int S,
     int part_rows, float* __restrict__ h, int h_seq_stride, const int* __restrict__ rows,
     const int* __restrict__ part_slot, const int* __restrict__ n_rows, int n_rows_host,
@@ -231,7 +299,6 @@ __global__ __launch_bounds__(256) void resid_norm_rows_kernel(
   const int id = rows[slot];
   const float* r = resid + ((size_t)(id >> 16) * resid_seq_stride + (id & 0xffff)) * d;
   float* y = h + ((size_t)(id >> 16) * h_seq_stride + (id & 0xffff)) * d;
-  // the partial rows are indexed by the slot the row had when the GEMM ran
   const float* p0 = part + (size_t)(part_slot ? part_slot[slot] : slot) * d;
   const size_t pstride = (size_t)part_rows * d;
   float ss = 0.f;
@@ -262,14 +329,21 @@ void launch_resid_norm_rows(bool f16, const float* resid, int resid_seq_stride, 
                             const int* part_slot, const int* n_rows, int n_rows_host, int max_rows,
                             const float* gain, float eps, int d, bf16_t* xp, int KC,
                             hipStream_t st) {
-  if (f16)
-    hipLaunchKernelGGL(resid_norm_rows_kernel<true>, dim3(max_rows), dim3(256), 0, st,
-                       resid, resid_seq_stride, part, S, part_rows, h, h_seq_stride, rows, part_slot,
-                       n_rows, n_rows_host, gain, eps, d, xp, KC);
-  else
-    hipLaunchKernelGGL(resid_norm_rows_kernel<false>, dim3(max_rows), dim3(256), 0, st,
-                       resid, resid_seq_stride, part, S, part_rows, h, h_seq_stride, rows, part_slot,
-                       n_rows, n_rows_host, gain, eps, d, xp, KC);
+#define VLAC_RN(K)                                                                               \
+  hipLaunchKernelGGL(K, dim3(max_rows), dim3(256), 0, st, resid, resid_seq_stride, part, S,      \
+                     part_rows, h, h_seq_stride, rows, part_slot, n_rows, n_rows_host, gain, eps, \
+                     d, xp, KC)
+  if (d <= 4096) {
+    if (f16) VLAC_RN((resid_norm_rows_kernel<true, 4>));
+    else VLAC_RN((resid_norm_rows_kernel<false, 4>));
+  } else if (d <= 8192) {
+    if (f16) VLAC_RN((resid_norm_rows_kernel<true, 8>));
+    else VLAC_RN((resid_norm_rows_kernel<false, 8>));
+  } else {
+    if (f16) VLAC_RN(resid_norm_rows_long_kernel<true>);
+    else VLAC_RN(resid_norm_rows_long_kernel<false>);
+  }
+#undef VLAC_RN
 }
 
 // Final RMSNorm of every row alive at the last layer, fp32 out [B, L, d].
@@ -303,32 +377,38 @@ void launch_final_hidden(const float* src, int seq_stride, const int* rows, cons
 }
 
 // ---------------------------------------------------------------------------
-// Greedy token: argmax over the vocabulary, ties -> lower id.  grid (B).
+// Greedy token: argmax over the vocabulary, ties -> lower id.  grid (B), 1024 threads.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits,
-                                                     size_t logits_stride, int vocab,
-                                                     int32_t* __restrict__ out, int out_stride,
-                                                     int32_t* __restrict__ out2) {
-  __shared__ float bv[4];
-  __shared__ int bi[4];
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits,
+                                                      size_t logits_stride, int vocab,
+                                                      int32_t* __restrict__ out, int out_stride,
+                                                      int32_t* __restrict__ out2) {
+  __shared__ float bv[16];
+  __shared__ int bi[16];
   const int b = blockIdx.x, tid = threadIdx.x;
   const float* x = logits + (size_t)b * logits_stride;
   float best = -INFINITY;
   int idx = 0x7fffffff;
-  for (int i = tid; i < vocab; i += 256) {
-    const float v = x[i];
+  auto take = [&](float v, int i) {
     if (v > best || (v == best && i < idx)) { best = v; idx = i; }
+  };
+  // 16-byte loads where the row allows them (base and stride multiples of 4 floats)
+  const bool vec = ((((size_t)x) & 15) == 0);
+  const int nv = vec ? (vocab & ~3) : 0;
+  for (int i = tid * 4; i < nv; i += 4096) {
+    const float4 v = *(const float4*)(x + i);
+    take(v.x, i); take(v.y, i + 1); take(v.z, i + 2); take(v.w, i + 3);
   }
+  for (int i = nv + tid; i < vocab; i += 1024) take(x[i], i);
   for (int o = 32; o > 0; o >>= 1) {
     const float v = __shfl_xor(best, o);
     const int i = __shfl_xor(idx, o);
-    if (v > best || (v == best && i < idx)) { best = v; idx = i; }
+    take(v, i);
   }
   if ((tid & 63) == 0) { bv[tid >> 6] = best; bi[tid >> 6] = idx; }
   __syncthreads();
   if (tid == 0) {
-    for (int k = 1; k < 4; ++k)
-      if (bv[k] > best || (bv[k] == best && bi[k] < idx)) { best = bv[k]; idx = bi[k]; }
+    for (int k = 1; k < 16; ++k) take(bv[k], bi[k]);
     if (idx == 0x7fffffff) idx = 0;  // every logit NaN: still a valid id
     out[(size_t)b * out_stride] = idx;
     if (out2) out2[b] = idx;
@@ -337,7 +417,7 @@ __global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ l
 
 void launch_argmax(const float* logits, size_t logits_stride, int B, int vocab, int32_t* out,
                    int out_stride, int32_t* out2, hipStream_t st) {
-  hipLaunchKernelGGL(argmax_kernel, dim3(B), dim3(256), 0, st, logits, logits_stride, vocab, out,
+  hipLaunchKernelGGL(argmax_kernel, dim3(B), dim3(1024), 0, st, logits, logits_stride, vocab, out,
                      out_stride, out2);
 }
 
