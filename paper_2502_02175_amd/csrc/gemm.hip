@@ -29,108 +29,7 @@
 //  * Workgroup ids are dealt round-robin to the 8 XCDs; row blocks of one weight
 //    tile are mapped to the same XCD so that they share its L2.
 #include <cstring>
-#include "common.h"
-
-struct GemmArgs {
-  const uint4* wp;    // weights, fragment order, 64 uint4 per tile
-  const uint4* xp;    // activations, fragment order
-  const uint4* zero_tile;  // 1 KiB of zeros
-  NormIn norm;        // fused RMSNorm of the input rows (few-rows kernel only)
-  int NB;             // weight row blocks (32 output features each)
-  int KS;             // K steps (64 k = 4 tiles each)
-  const int* n_rows;  // device: rows in use
-  int n_rows_val;     // >= 0: the row count is known on the host, n_rows is not read
-  int S, MB, P;       // split-K factor, row blocks, weight tiles * S
-  float* partial;
-  int* counters;
-  GemmEpi e;
-};
-
-__device__ inline float silu_f(float x) { return x / (1.f + __expf(-x)); }
-
-template <int EPI, bool F16>
-__device__ inline void epilogue_tile(const GemmEpi& e, int nb, int slot, int id, int g,
-                                     const f32x16& acc) {
-  const int b = id >> 16, pos = id & 0xffff;
-  if constexpr (EPI == EPI_QKV) {
-    const int hd = e.head_dim, bph = hd >> 5;
-    const int nbq = e.n_q_heads * bph, nbk = e.n_kv_heads * bph;
-    const size_t head_elems = (size_t)e.max_seq * hd;
-    bf16_t* kvl = e.kv + (size_t)b * e.kv_stream_stride + e.kv_layer_off;
-    if (nb < nbq + nbk) {
-      // query or key block: rows 0..15 hold features f, rows 16..31 their rotary partners f + hd/2
-      const bool isq = nb < nbq;
-      const int nbl = isq ? nb : nb - nbq, head = nbl / bph, sb = nbl % bph;
-      bf16_t* dst;
-      int row;  // row of the fragment-ordered destination
-      if (isq) {
-        dst = e.qbuf + ((size_t)(slot >> 5) * e.n_q_heads + head) * (size_t)(hd >> 4) * 512;
-        row = slot & 31;
-      } else {
-        dst = kvl + (size_t)head * head_elems + (size_t)(pos >> 5) * (hd >> 4) * 512;
-        row = pos & 31;
-      }
-#pragma unroll
-      for (int q4 = 0; q4 < 2; ++q4) {
-        const int f1 = 16 * sb + 8 * q4 + 4 * g;
-        const float4 c4 = *(const float4*)(e.rope_cos + (size_t)pos * (hd >> 1) + f1);
-        const float4 s4 = *(const float4*)(e.rope_sin + (size_t)pos * (hd >> 1) + f1);
-        const float cs[4] = {c4.x, c4.y, c4.z, c4.w}, sn[4] = {s4.x, s4.y, s4.z, s4.w};
-        float o1[4], o2[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const float x1 = acc[4 * q4 + k], x2 = acc[4 * (q4 + 2) + k];
-          o1[k] = x1 * cs[k] - x2 * sn[k];
-          o2[k] = x2 * cs[k] + x1 * sn[k];
-        }
-        const int f2 = f1 + (hd >> 1);
-        *(uint2*)(dst + (size_t)(f1 >> 4) * 512 + ((row + (((f1 >> 3) & 1) << 5)) << 3) + (f1 & 7)) =
-            make_uint2(pack_op2<F16>(o1[0], o1[1]), pack_op2<F16>(o1[2], o1[3]));
-        *(uint2*)(dst + (size_t)(f2 >> 4) * 512 + ((row + (((f2 >> 3) & 1) << 5)) << 3) + (f2 & 7)) =
-            make_uint2(pack_op2<F16>(o2[0], o2[1]), pack_op2<F16>(o2[2], o2[3]));
-      }
-    } else {
-      // value block -> the cache's V tile: per 32 positions and 32 features, the
-      // operand of the P.V product (key order inside a tile follows the score tile)
-      const int nbl = nb - nbq - nbk, head = nbl / bph, ib = nbl % bph;
-      const int pt = pos >> 5, pl = pos & 31, s = pl >> 4, r16 = pl & 15;
-      const int gp = (r16 & 7) >> 2, ep = 4 * (r16 >> 3) + (r16 & 3);
-      bf16_t* dst = kvl + (size_t)(e.n_kv_heads + head) * head_elems +
-                    (((size_t)pt * bph + ib) * 2 + s) * 512 + (size_t)(32 * gp) * 8 + ep;
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4)
-#pragma unroll
-        for (int k = 0; k < 4; ++k) dst[(8 * q4 + 4 * g + k) * 8] = f2op<F16>(acc[4 * q4 + k]);
-    }
-  } else if constexpr (EPI == EPI_RESID) {
-    const int hpos = e.h_compact ? 0 : pos;
-    const float* rs = e.resid_src + ((size_t)b * e.resid_seq_stride + hpos) * e.d_model + nb * 32 + 4 * g;
-    float* hp = e.h + ((size_t)b * e.h_seq_stride + hpos) * e.d_model + nb * 32 + 4 * g;
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      float4 r = *(const float4*)(rs + 8 * q4);
-      r.x += acc[4 * q4]; r.y += acc[4 * q4 + 1]; r.z += acc[4 * q4 + 2]; r.w += acc[4 * q4 + 3];
-      *(float4*)(hp + 8 * q4) = r;
-    }
-  } else if constexpr (EPI == EPI_SWIGLU) {
-    // rows 0..15 of the block: gate features, rows 16..31: the matching up features
-#pragma unroll
-    for (int q4 = 0; q4 < 2; ++q4) {
-      const int ff = 16 * nb + 8 * q4 + 4 * g;
-      float o[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) o[k] = silu_f(acc[4 * q4 + k]) * acc[4 * (q4 + 2) + k];
-      *(uint2*)(e.xf + frag_off(slot, ff, e.kc_f)) =
-          make_uint2(pack_op2<F16>(o[0], o[1]), pack_op2<F16>(o[2], o[3]));
-    }
-  } else {  // EPI_LOGITS: slot is the stream
-    float* out = e.logits + (size_t)slot * e.logits_stride + nb * 32 + 4 * g;
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4)
-      *(float4*)(out + 8 * q4) =
-          make_float4(acc[4 * q4], acc[4 * q4 + 1], acc[4 * q4 + 2], acc[4 * q4 + 3]);
-  }
-}
+#include "gemm_epi.h"
 
 // Main loop, split-K hand-over and epilogue for a row block with exactly NA active
 // 32-row tiles (a template parameter, so that every loop is unrolled without guards
@@ -649,6 +548,10 @@ bool gemm_can_fuse_norm(int n_rows_host, int decode_pos, int kpad) {
          (size_t)(kpad / 8) * n_rows_host * 16 <= kStageBytes;
 }
 
+// From this many rows on (the capacity of the launch: streams x tokens) the GEMMs are
+// matrix-core bound and go to the kernel built for that.
+static const int kTallRows = 1024;
+
 int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, const bf16_t* xp,
                  const int* n_rows, int n_rows_host, int rows_cap, const GemmEpi& e, hipStream_t st,
                  const NormIn* norm) {
@@ -693,6 +596,8 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, 
       if (c->f16) launch_few<true, X_GLOBAL>(epi, a, a.P, 0, st);
       else launch_few<false, X_GLOBAL>(epi, a, a.P, 0, st);
     }
+  } else if (rows_cap >= kTallRows) {
+    launch_gemm_tall(c->f16, epi, a, rows_cap, st);
   } else {
     constexpr int MT = 4;
     const int tiles = (n_blocks + 3) / 4;

@@ -1,0 +1,190 @@
+// Recomputed-row GEMMs with MANY rows (batched streams: thousands of rows per layer;
+// Alg. 2 of VLA-Cache over the rows outside P_reuse of every stream at once).
+//
+// With thousands of rows the weights are no longer the traffic: the GEMM is bound by the
+// matrix cores, and what has to be kept small is the operand traffic and the number of
+// other instructions per MFMA.
+//
+//  * A workgroup is 8 waves (two per SIMD, so that one computes while the other waits);
+//    a wave owns 2 blocks of 32 output features over all 4 row tiles of its row block:
+//    8 accumulator tiles, and one k-tile is 8 MFMAs for 2 weight tiles + 4 activation
+//    tiles fetched.  The workgroup tile is 512 features x 128 rows.
+//  * Operands are in fragment order (common.h).  Weight tiles go global -> registers (no
+//    other wave wants them): a ring of 6 k-tiles, the slot of a k-tile is refilled with
+//    the tile 6 ahead as soon as its MFMAs are issued, so that loads are spread over the
+//    step and have a step and a half of matrix work to land (L2 latency: the row blocks
+//    of one weight tile run side by side on one XCD, all but one of them hit its L2).
+//  * Activation tiles are shared by the 8 waves through LDS, 64 k per step, and are
+//    copied global -> LDS directly (global_load_lds_dwordx4: lane l's 16 bytes land at
+//    base + 16 l, which is the fragment order itself), two steps ahead, into a ring of 3
+//    buffers: no staging registers, no LDS store instructions, one barrier per step.
+//  * No split of K: tiles x row blocks fill the chip by themselves.
+#include "gemm_epi.h"
+
+namespace {
+
+constexpr int NF = 2;       // feature blocks per wave
+constexpr int TALL_W = 8;   // waves per workgroup
+constexpr int XBUF = 3;     // LDS buffers of 4 row tiles x 4 k-tiles
+
+template <int NA, int EPI, bool F16>
+__device__ __forceinline__ void tall_body(const GemmArgs& a, uint4* lds, int tile, int mb, int n_rows) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int row0 = mb * 128;
+  const int KC = 4 * a.KS, KS = a.KS;
+  const int nb0 = tile * (TALL_W * NF) + w * NF;
+  const uint4* wsrc[NF];
+#pragma unroll
+  for (int fb = 0; fb < NF; ++fb)
+    wsrc[fb] = a.wp + (size_t)min(nb0 + fb, a.NB - 1) * KC * 64 + lane;
+  // this wave copies activation tiles j = 2 w, 2 w + 1 of a step's 16 (row tile j / 4, k-tile j % 4)
+  const int mt0 = w >> 1, c0 = (w & 1) * 2;
+  const uint4* xsrc = a.xp + ((size_t)((row0 >> 5) + mt0) * KC + c0) * 64 + lane;
+  uint4* xdst = lds + mt0 * 256 + c0 * 64;
+
+  f32x16 acc[NF][NA];
+#pragma unroll
+  for (int fb = 0; fb < NF; ++fb)
+#pragma unroll
+    for (int mt = 0; mt < NA; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[fb][mt][i] = 0.f;
+
+  uint4 W[6][NF];
+  const int last_kt = 4 * KS - 1;
+  auto load_w = [&](int kt, uint4(&dst)[NF]) {
+    const size_t k = (size_t)min(kt, last_kt) * 64;
+#pragma unroll
+    for (int fb = 0; fb < NF; ++fb) dst[fb] = wsrc[fb][k];
+  };
+  // Activation tiles of step i -> LDS buffer i % 3 (row tiles past the block's last are
+  // never read and not copied).  The copies are written as inline assembly on purpose:
+  // the compiler treats its own LDS-direct loads as possibly aliasing every LDS read and
+  // drains the whole load queue (the weight ring with it) before the next one.  So the
+  // compiler does not know about these two loads per step, and the waits for them are
+  // placed by hand (loads return in issue order, and nothing moves across the asm
+  // statements, so the count of younger loads is fixed: see the step macro).  Its own
+  // waits for the weight tiles can only come out longer than needed, never shorter.
+  const uint32_t xdst0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)xdst);
+  auto copy_x = [&](int i, int buf) {
+    if (mt0 < NA) {
+      const uint4* src = xsrc + (size_t)min(i, KS - 1) * 256;
+      const uint32_t dst = xdst0 + buf * 16384;
+      asm volatile(
+          "s_mov_b32 m0, %0\n\t"
+          "s_nop 0\n\t"
+          "global_load_lds_dwordx4 %1, off\n\t"
+          "global_load_lds_dwordx4 %1, off offset:1024"  // next k-tile: + 1 KiB on both sides
+          :
+          : "s"(dst), "v"(src)
+          : "memory", "m0");
+    }
+  };
+  auto ktile = [&](int i, int c, int buf, uint4(&Ws)[NF]) {
+    uint4 xf[NA];
+#pragma unroll
+    for (int mt = 0; mt < NA; ++mt) xf[mt] = lds[(buf * 4 + mt) * 256 + c * 64 + lane];
+#pragma unroll
+    for (int fb = 0; fb < NF; ++fb)
+#pragma unroll
+      for (int mt = 0; mt < NA; ++mt) acc[fb][mt] = mfma32<F16>(Ws[fb], xf[mt], acc[fb][mt]);
+    load_w(4 * i + c + 6, Ws);
+  };
+  // Step i at phase ph = i % 3 of the unrolled loop: its k-tiles sit in slots
+  // (4 ph + c) % 6 and its activation tiles in LDS buffer ph.  They were asked for at the
+  // start of step i - 2; behind them this wave has issued 2 x 8 weight loads and the two
+  // copies of step i + 1, so "at most 18 loads outstanding" means they have landed; the
+  // barrier then makes that true for the copies of all 8 waves, and says that every wave
+  // is done with step i - 1, whose buffer takes the tiles of step i + 2.
+#define VLAC_TALL_STEP(i, ph, s0, s1, s2, s3)                \
+  {                                                          \
+    asm volatile("s_waitcnt vmcnt(18)" ::: "memory");        \
+    __syncthreads();                                         \
+    copy_x((i) + 2, ((ph) + 2) % 3);                         \
+    ktile((i), 0, ph, W[s0]);                                \
+    ktile((i), 1, ph, W[s1]);                                \
+    ktile((i), 2, ph, W[s2]);                                \
+    ktile((i), 3, ph, W[s3]);                                \
+  }
+
+  copy_x(0, 0);
+  copy_x(1, 1);
+#pragma unroll
+  for (int kt = 0; kt < 6; ++kt) load_w(kt, W[kt]);
+  asm volatile("s_waitcnt vmcnt(12)" ::: "memory");  // both copies; the 12 weight loads fly on
+  int i = 0;
+  for (; i + 3 <= KS; i += 3) {
+    VLAC_TALL_STEP(i, 0, 0, 1, 2, 3)
+    VLAC_TALL_STEP(i + 1, 1, 4, 5, 0, 1)
+    VLAC_TALL_STEP(i + 2, 2, 2, 3, 4, 5)
+  }
+  if (i < KS) {
+    VLAC_TALL_STEP(i, 0, 0, 1, 2, 3)
+    if (i + 1 < KS) VLAC_TALL_STEP(i + 1, 1, 4, 5, 0, 1)
+  }
+#undef VLAC_TALL_STEP
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no copy outlives the loop
+
+  const int g = lane >> 5;
+#pragma unroll
+  for (int mt = 0; mt < NA; ++mt) {
+    const int slot = row0 + mt * 32 + (lane & 31);
+    if (slot < n_rows) {
+      const int id = (EPI == EPI_LOGITS) ? 0 : a.e.rows[slot];
+#pragma unroll
+      for (int fb = 0; fb < NF; ++fb)
+        if (nb0 + fb < a.NB) epilogue_tile<EPI, F16>(a.e, nb0 + fb, slot, id, g, acc[fb][mt]);
+    }
+  }
+}
+
+template <int EPI, bool F16>
+__global__ __launch_bounds__(512) void gemm_tall_kernel(GemmArgs a) {
+  __shared__ uint4 lds[XBUF * 4 * 256];  // 3 stages of 4 activation tiles x 4 k-tiles
+  // workgroup id -> (weight tile, row block); id % 8 is the XCD, and the row blocks of one
+  // weight tile follow each other on the same XCD.  (One workgroup per work item, sized
+  // for the largest possible row count: measured against a persistent grid that deals the
+  // items of the actual row count round-robin, the hardware's dynamic dispatch wins, and
+  // the workgroups that find no rows cost next to nothing.)
+  const int y = blockIdx.x >> 3;
+  const int mb = y % a.MB, tile = (y / a.MB) * 8 + (blockIdx.x & 7);
+  if (tile >= a.P) return;
+  const int n_rows = a.n_rows_val >= 0 ? a.n_rows_val : *a.n_rows;
+  const int row0 = mb * 128;
+  if (row0 >= n_rows) return;
+  switch (min(4, (n_rows - row0 + 31) >> 5)) {
+    case 1: tall_body<1, EPI, F16>(a, lds, tile, mb, n_rows); break;
+    case 2: tall_body<2, EPI, F16>(a, lds, tile, mb, n_rows); break;
+    case 3: tall_body<3, EPI, F16>(a, lds, tile, mb, n_rows); break;
+    default: tall_body<4, EPI, F16>(a, lds, tile, mb, n_rows); break;
+  }
+}
+
+template <bool F16>
+void launch_tall(int epi, const GemmArgs& a, int grid, hipStream_t st) {
+  switch (epi) {
+    case EPI_QKV:
+      hipLaunchKernelGGL((gemm_tall_kernel<EPI_QKV, F16>), dim3(grid), dim3(512), 0, st, a);
+      break;
+    case EPI_RESID:
+      hipLaunchKernelGGL((gemm_tall_kernel<EPI_RESID, F16>), dim3(grid), dim3(512), 0, st, a);
+      break;
+    case EPI_SWIGLU:
+      hipLaunchKernelGGL((gemm_tall_kernel<EPI_SWIGLU, F16>), dim3(grid), dim3(512), 0, st, a);
+      break;
+    default:
+      hipLaunchKernelGGL((gemm_tall_kernel<EPI_LOGITS, F16>), dim3(grid), dim3(512), 0, st, a);
+      break;
+  }
+}
+
+}  // namespace
+
+void launch_gemm_tall(bool f16, int epi, GemmArgs& a, int rows_cap, hipStream_t st) {
+  a.S = 1;
+  a.MB = (rows_cap + 127) / 128;
+  a.P = (a.NB + TALL_W * NF - 1) / (TALL_W * NF);  // weight tiles of 512 output features
+  const int grid = ((a.P + 7) / 8) * 8 * a.MB;
+  if (f16) launch_tall<true>(epi, a, grid, st);
+  else launch_tall<false>(epi, a, grid, st);
+}
