@@ -2,8 +2,9 @@
 // Alg. 2 of VLA-Cache over the rows outside P_reuse of every stream at once).
 //
 // With thousands of rows the weights are no longer the traffic: the GEMM is bound by the
-// matrix cores, and what has to be kept small is the operand traffic and the number of
-// other instructions per MFMA.
+// matrix cores, and behind them by what the L2 delivers to a CU (measured here: about 20
+// bytes per clock and CU, whatever the access pattern), so the operand bytes fetched per
+// MFMA and the number of other instructions per MFMA are what has to be kept small.
 //
 //  * A workgroup is 8 waves (two per SIMD, so that one computes while the other waits);
 //    a wave owns 2 blocks of 32 output features over all 4 row tiles of its row block:
@@ -19,6 +20,12 @@
 //    base + 16 l, which is the fragment order itself), two steps ahead, into a ring of 3
 //    buffers: no staging registers, no LDS store instructions, one barrier per step.
 //  * No split of K: tiles x row blocks fill the chip by themselves.
+//  * Tried and measured, not kept: 4 waves x 4 feature blocks (one wave per SIMD: 12%
+//    slower), staging the activation tiles through registers (the extra registers and
+//    LDS stores cost 3%), a 256 x 256 tile whose weight tiles are fetched by two waves
+//    each (the second fetch hits L1, but the kernel is 5% slower), a persistent grid that
+//    deals the work items of the actual row count round-robin (2% slower than letting
+//    the hardware dispatch one workgroup per item).
 #include "gemm_epi.h"
 
 namespace {

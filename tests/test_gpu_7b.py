@@ -207,3 +207,74 @@ def test_gqa_32_streams_properties():
         np.testing.assert_array_equal(t_same, t_full)
     finally:
         gm.close()
+
+
+def test_frame_stream_with_filter_and_layer_adaptive_reuse():
+    """The streamed configuration: a textured static background with a 48 x 48 px box
+    moving 6 px per frame (85-90% of the patches static), task-relevance filter and
+    layer-adaptive reuse on, at the 7B layer shape with 3 layers.  Every step runs
+    Alg. 1, the layer ratio, the sparse prefill with per-layer reuse counts and two
+    decode passes on the GPU, each against the oracle; the statistics the plan of a step
+    is made from are the oracle's (no expected value comes from the GPU)."""
+    TOL = TOLS["f16"]
+    cfg = CFG.with_layers(3)
+    n_frames, tau_task = 5, 0.5
+    frames = synth.moving_box_stream(H, H, n_frames, seed=21)
+    wp = synth.projection_matrix(cfg.d_model, PATCH, 22)
+    txt = synth.round_bf16(synth.text_embeddings(N_TXT, cfg.d_model, 23))
+    emb = [np.concatenate([synth.round_bf16(synth.visual_embeddings(f, PATCH, wp)), txt]) for f in frames]
+    om = oracle_model(cfg, seed=5, gain_jitter=0.1)
+    gm = GpuModel(cfg, seed=5, max_batch=1, max_seq=320, gain_jitter=0.1)
+    try:
+        cache = O.new_cache(cfg, 320)
+        want = O.dense_forward(om, emb[0], N_VIS, cache)
+        got = gm.prefill(emb[0][None], N_VIS)
+        assert np.abs(got["logits"][0] - want["logits"]).max() <= TOL
+        n_static_seen, varied = [], False
+        for t in range(1, n_frames):
+            # The oracle's statistics of step t - 1.  A random-init decoder has a flat
+            # entropy profile over depth (alpha would be 0 everywhere), so the profile handed
+            # to the planner is sharpened with depth, a^l -> (a^l)^(1 + 4 l): entropy then
+            # falls with depth, as the method assumes (Sec. 3.4).
+            stats = np.stack([want["attn_mean"][l] ** (1.0 + 4.0 * l)
+                              for l in range(cfg.n_layers)]).astype(np.float32)
+            # a gain that takes the largest cumulative entropy drop to alpha = 0.6, so that
+            # the reuse counts differ over depth whatever the random-init profile is
+            ent = O.layer_entropy(stats)
+            r_cum = np.cumsum([0.0] + [(ent[l - 1] - ent[l]) / ent[l - 1] for l in range(1, len(ent))])
+            gain = float(0.6 / r_cum.max()) if r_cum.max() > 1e-6 else 8.0
+            p_final, order, per_layer, alpha = O.plan_step(frames[t - 1], frames[t], PATCH, 249, 250,
+                                                           TOP_K, stats, tau_task, gain)
+            counts = [len(s) for s in per_layer]
+            sel = gm.select(frames[t - 1][None], frames[t][None], PATCH, 249, 250, TOP_K,
+                            stats[:, None], tau_task)
+            assert sel["idx"][0] == p_final and sel["order"][0] == order
+            g_alpha, g_counts = gm.layer_ratio(stats[:, None], gain, [len(p_final)])
+            np.testing.assert_allclose(g_alpha[0], alpha, atol=1e-6)
+            for l in range(cfg.n_layers):
+                frac = float(np.float32(alpha[l])) * len(p_final)
+                assert abs(int(g_counts[0, l]) - counts[l]) <= (0 if abs(frac - round(frac)) > 1e-3 else 1)
+            n_static_seen.append(len(O.select_static(frames[t - 1], frames[t], PATCH, 249, 250, N_VIS)))
+            varied |= len(set(counts)) > 1
+            want = O.sparse_forward(om, emb[t], N_VIS, cache, per_layer)
+            got = gm.prefill(emb[t][None], N_VIS, [order], [counts])
+            alive = ~np.isnan(want["hidden"][:, 0])
+            e_h = np.abs(got["hidden"][0][alive] - want["hidden"][alive]).max()
+            e_l = np.abs(got["logits"][0] - want["logits"]).max()
+            print("\nframe %d: %d static, reuse per layer %s, max-abs hidden %.4g logits %.4g"
+                  % (t, n_static_seen[-1], counts, e_h, e_l))
+            assert e_h <= TOL and e_l <= TOL
+            assert np.all(np.isnan(got["hidden"][0][~alive]))
+            np.testing.assert_allclose(got["attn_mean"][:, 0], want["attn_mean"], atol=1e-4, rtol=2e-2)
+            if margin(want["logits"]) > 2 * TOL:
+                assert int(got["token"][0]) == want["token"]
+            toks, logits = O.decode(om, cache, L, want["token"], 2, return_logits=True)
+            gt, gl = gm.decode(1, L, 2, [want["token"]])
+            assert np.abs(gl[0] - logits).max() <= TOL
+            if all(margin(x) > 2 * TOL for x in logits):
+                assert gt[0].tolist() == toks
+        assert varied                                        # reuse counts did differ over depth
+        # the stream is what the configuration says: 85-90% of the patches static
+        assert all(0.80 * N_VIS <= n <= 0.95 * N_VIS for n in n_static_seen), n_static_seen
+    finally:
+        gm.close()
