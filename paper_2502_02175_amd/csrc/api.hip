@@ -149,7 +149,14 @@ int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out) {
   A_(rank, (size_t)mr);
   A_(m_layer, (size_t)mb * nl);
   A_(n_rows_bl, (size_t)mb * nl);
-  A_(statp, (size_t)mb * m.n_q_heads * ctx->stat_tt * ms);
+  {
+    // either one layer's sums for any number of text tiles, or (text of at most 96 tokens)
+    // all layers' sums, which one kernel adds up after the last layer
+    const size_t one = (size_t)mb * m.n_q_heads * ctx->stat_tt * ms;
+    const size_t all = (size_t)nl * mb * m.n_q_heads * kStatDeferTT * ms;
+    ctx->statp_floats = one > all ? one : all;
+  }
+  A_(statp, ctx->statp_floats);
   A_(stat_counters, mb);
   A_(logits, (size_t)mb * m.vocab);
   A_(tokens, mb);
@@ -541,6 +548,8 @@ int vlac_sparse_prefill(vlac_ctx* ctx, const float* embeds, int B, int L_v, int 
                            m.max_seq, ctx->rows + (size_t)(nl - 1) * ctx->max_rows, nullptr,
                            ctx->n_rows + (nl - 1), n_host, rows_cap, nullptr, m.rms_eps, m.d_model,
                            ctx->xa, ctx->kpad_d / 16, st);
+  if (out_attn_mean && attention_defers_stats(ctx, B, L_v, L_t))
+    launch_stats_reduce(ctx, B, L_v, L_t, out_attn_mean, st);
   if (out_hidden)
     launch_final_hidden(ctx->h, m.max_seq, ctx->rows + (size_t)(nl - 1) * ctx->max_rows,
                         ctx->n_rows + (nl - 1), rows_cap, ctx->g_final, m.rms_eps, m.d_model,

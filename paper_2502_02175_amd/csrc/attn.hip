@@ -39,9 +39,10 @@ struct AttnArgs {
   float scale_log2e;    // log2(e) / sqrt(head_dim)
   float* attn_mean;     // [B, L_v] of this layer or NULL
   int attn_mean_stride; // elements between streams
-  float* statp;         // [B][Hq][TT][lv_pad]
+  float* statp;         // [B][Hq][TT][lv_pad] (of this layer, if the reduction is deferred)
   int TT, lv_pad;
   int* stat_counters;   // [B]
+  int defer_stats;      // the parked sums are added up by stats_reduce_kernel after the last layer
 };
 
 template <int HD, bool F16>
@@ -197,10 +198,11 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a) {
   const bool is_text = valid && pos >= a.L_v;
   float* park = a.statp + (((size_t)b * a.n_q_heads + h) * a.TT + tt) * a.lv_pad;
   const int n_vt = (a.L_v + 31) >> 5;
+  if (w < n_vt) load_k(w, kf);
   for (int kt = w; kt < n_vt; kt += 4) {
     f32x16 s;
-    load_k(kt, kf);
     scores(kf, s);
+    if (kt + 4 < n_vt) load_k(kt + 4, kf);  // the next tile flies during the arithmetic
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       float pv = is_text ? exp2f(s[i] * a.scale_log2e - m_fin) * inv_fin : 0.f;
@@ -210,10 +212,18 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a) {
       s[i] = pv;
     }
     if (j == 0) {
+      if (a.defer_stats) {  // read by a later kernel: plain stores
 #pragma unroll
-      for (int i = 0; i < 16; ++i) st_coherent(park + 32 * kt + 8 * (i >> 2) + 4 * g + (i & 3), s[i]);
+        for (int q4 = 0; q4 < 4; ++q4)
+          *(float4*)(park + 32 * kt + 8 * q4 + 4 * g) =
+              make_float4(s[4 * q4], s[4 * q4 + 1], s[4 * q4 + 2], s[4 * q4 + 3]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) st_coherent(park + 32 * kt + 8 * (i >> 2) + 4 * g + (i & 3), s[i]);
+      }
     }
   }
+  if (a.defer_stats) return;
   stores_done();
   __syncthreads();
   if (tid == 0) {
@@ -224,14 +234,71 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a) {
   }
   __syncthreads();
   if (!s_last) return;
+  // the parked sums of all heads and text tiles, in fixed order, 16 loads in flight at a time
   const float norm = 1.f / ((float)a.n_q_heads * (float)a.L_t);
+  const int n_part = a.n_q_heads * n_tt;
+  const float* part0 = a.statp + (size_t)b * a.n_q_heads * a.TT * a.lv_pad;
   for (int v = tid; v < a.L_v; v += 256) {
     float acc = 0.f;
-    for (int hh = 0; hh < a.n_q_heads; ++hh)
-      for (int t = 0; t < n_tt; ++t)
-        acc += ld_coherent(a.statp + (((size_t)b * a.n_q_heads + hh) * a.TT + t) * a.lv_pad + v);
+    for (int p0 = 0; p0 < n_part; p0 += 16) {
+      float t[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int p = min(p0 + i, n_part - 1), hh = p / n_tt, tq = p - hh * n_tt;
+        t[i] = ld_coherent(part0 + ((size_t)hh * a.TT + tq) * a.lv_pad + v);
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc += (p0 + i < n_part) ? t[i] : 0.f;
+    }
     a.attn_mean[(size_t)b * a.attn_mean_stride + v] = acc * norm;
   }
+}
+
+// The statistic of all layers at once, after the last layer (text-to-vision attention
+// averaged over heads and text queries, Eq. avistext): adds the sums that the attention
+// kernels of the prefill parked, [layer][B][Hq][TT][lv_pad], over heads and text tiles in
+// fixed order.  grid (layers, B); slot_off is [layers][slot_stride] (first slot of every
+// stream at every layer), from which the number of text tiles follows as in the kernel.
+__global__ __launch_bounds__(256) void stats_reduce_kernel(const float* __restrict__ statp,
+                                                           const int* __restrict__ slot_off,
+                                                           int slot_stride, int B, int n_q_heads,
+                                                           int TT, int lv_pad, int L_v, int L_t,
+                                                           float* __restrict__ attn_mean) {
+  const int layer = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int* so = slot_off + (size_t)layer * slot_stride;
+  const int n_b = so[b + 1] - so[b];
+  const int x_first = (n_b - L_t) >> 5;
+  const int n_tt = ((n_b - 1) >> 5) - x_first + 1;
+  const int n_part = n_q_heads * n_tt;
+  const float* part0 = statp + ((size_t)layer * B + b) * n_q_heads * TT * lv_pad;
+  const float norm = 1.f / ((float)n_q_heads * (float)L_t);
+  for (int v = tid; v < L_v; v += 256) {
+    float acc = 0.f;
+    for (int p0 = 0; p0 < n_part; p0 += 16) {
+      float t[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int p = min(p0 + i, n_part - 1), hh = p / n_tt, tq = p - hh * n_tt;
+        t[i] = part0[((size_t)hh * TT + tq) * lv_pad + v];
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc += (p0 + i < n_part) ? t[i] : 0.f;
+    }
+    attn_mean[((size_t)layer * B + b) * L_v + v] = acc * norm;
+  }
+}
+
+bool attention_defers_stats(const vlac_ctx* c, int B, int L_v, int L_t) {
+  // text rows of a stream lie in at most ceil(L_t / 32) + 1 tiles of 32 slots
+  const int n_tt_max = (L_t + 31) / 32 + 1;
+  const size_t need = (size_t)c->cfg.n_layers * B * c->cfg.n_q_heads * kStatDeferTT * round_up(L_v > 0 ? L_v : 1, 32);
+  return L_t > 0 && L_v > 0 && n_tt_max <= kStatDeferTT && need <= c->statp_floats;
+}
+
+void launch_stats_reduce(vlac_ctx* c, int B, int L_v, int L_t, float* out_attn_mean, hipStream_t st) {
+  hipLaunchKernelGGL(stats_reduce_kernel, dim3(c->cfg.n_layers, B), dim3(256), 0, st, c->statp,
+                     c->slot_off, c->cfg.max_batch + 1, B, c->cfg.n_q_heads, kStatDeferTT,
+                     round_up(L_v, 32), L_v, L_t, out_attn_mean);
 }
 
 void launch_attention(vlac_ctx* c, int layer, int B, int rows_cap_per_stream, int L_v, int L_t,
@@ -256,9 +323,15 @@ void launch_attention(vlac_ctx* c, int layer, int B, int rows_cap_per_stream, in
   a.scale_log2e = 1.4426950408889634f / sqrtf((float)m.head_dim);
   a.attn_mean = out_attn_mean ? out_attn_mean + (size_t)layer * B * L_v : nullptr;
   a.attn_mean_stride = L_v;
-  a.statp = c->statp;
-  a.TT = c->stat_tt;
   a.lv_pad = round_up(L_v > 0 ? L_v : 1, 32);
+  a.defer_stats = out_attn_mean && decode_pos < 0 && attention_defers_stats(c, B, L_v, L_t);
+  if (a.defer_stats) {
+    a.TT = kStatDeferTT;
+    a.statp = c->statp + (size_t)layer * B * m.n_q_heads * kStatDeferTT * a.lv_pad;
+  } else {
+    a.TT = c->stat_tt;
+    a.statp = c->statp;
+  }
   a.stat_counters = c->stat_counters;
   dim3 grid((rows_cap_per_stream + 31) / 32, m.n_q_heads, B);
   if (m.head_dim == 128) {

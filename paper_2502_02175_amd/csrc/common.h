@@ -120,6 +120,7 @@ struct vlac_ctx {
   int* m_layer;     // [max_batch][n_layers]
   int* n_rows_bl;   // [n_layers][max_batch]
   float* statp;     // attention-statistic partial sums
+  size_t statp_floats;
   int stat_tt;      // text tiles per stream the statistic buffer provides for
   int* stat_counters;
   float* logits;    // [max_batch, vocab]
@@ -231,6 +232,13 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, 
 bool gemm_can_fuse_norm(int n_rows_host, int decode_pos, int kpad);
 
 // attn.hip
+// Text tiles per stream that the deferred statistic reduction provides for (text rows
+// of a stream lie in at most ceil(L_t / 32) + 1 tiles: L_t <= 96).
+static const int kStatDeferTT = 4;
+// true if the attention kernels of a prefill only park their sums and
+// launch_stats_reduce (once, after the last layer) writes out_attn_mean
+bool attention_defers_stats(const vlac_ctx* c, int B, int L_v, int L_t);
+void launch_stats_reduce(vlac_ctx* c, int B, int L_v, int L_t, float* out_attn_mean, hipStream_t st);
 void launch_attention(vlac_ctx* c, int layer, int B, int rows_cap_per_stream, int L_v, int L_t,
                       const int* rows, const int* slot_off, int decode_pos, bf16_t* kv,
                       float* out_attn_mean, hipStream_t st);
