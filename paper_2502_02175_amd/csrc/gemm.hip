@@ -276,7 +276,7 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(GemmArgs a) {
 enum { X_GLOBAL = 0, X_NORM4 = 1, X_NORM8 = 2 };
 
 template <int EPI, bool F16, int XMODE>
-__global__ __launch_bounds__(256) void gemm_few_kernel(GemmArgs a) {
+__global__ __launch_bounds__(256, XMODE == X_NORM8 ? 2 : 3) void gemm_few_kernel(GemmArgs a) {
   __shared__ float red[3][16][64];
   extern __shared__ uint4 xlds[];  // operand slices [k/8 - lo8][row]
   constexpr int U = 8;
