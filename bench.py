@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2", "c4", "c5"],
                     help="c2: the benchmark's workload (default); c4 / c5: the batched-stream shapes, "
                          "where the recomputed-row GEMMs are bound by the matrix cores")
+    ap.add_argument("--sweep", action="store_true",
+                    help="reused-token sweep on a synthetic frame stream (top-k x tau_task), with the "
+                         "paper's operation estimate beside the true count; prints its own JSON line")
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers than the model has")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=32)
@@ -84,6 +87,8 @@ def main():
 
     if args.workload != "c2":
         return batched(args, V, GpuModel, np, torch, synth, dev)
+    if args.sweep:
+        return sweep(args, V, GpuModel, np, torch, synth, dev)
 
     cfg = synth.CONFIGS["7b"]
     if args.layers:
@@ -388,6 +393,94 @@ def batched(args, V, GpuModel, np, torch, synth, dev):
                       "rows_recomputed": rows},
            "sweep": sweep, "roofline": roofline, "cpu_baseline": None,
            "paper_context": "paper: up to 1.7x latency speedup, ~15% control frequency, one RTX 4090, bf16"}
+    gm.close()
+    print(json.dumps(out))
+
+
+def sweep(args, V, GpuModel, np, torch, synth, dev):
+    """Reused-token sweep in the manner of the paper's sensitivity tables (top-k in
+    {50, 100, 150, 200}, tau_task in {0.2, 0.35, 0.5, 0.7}) on the streamed synthetic
+    configuration: a textured static background, a 48 px box moving 6 px per frame, 7B
+    shape, 7 action tokens.  Per setting: mean reused tokens, prefill and step latency,
+    and the operation count of the prefill by the paper's formula and as computed.
+    The layer-adaptive ratio is off (alpha = 1): with random-init weights the attention
+    entropy is flat over depth and the ratio would be 0 everywhere."""
+    from paper_2502_02175_amd import flops as FL
+    cfg = synth.CONFIGS["7b"]
+    if args.layers:
+        cfg = cfg.with_layers(args.layers)
+    H, patch, n_vis, n_txt, seed = 224, 14, 256, 32, 0
+    L, n_new, nl = n_vis + n_txt, N_ACTION - 1, cfg.n_layers
+    n_frames = 12
+    frames = synth.moving_box_stream(H, H, n_frames, seed=seed + 7)
+    wp = synth.projection_matrix(cfg.d_model, patch, seed + 1)
+    txt = synth.round_bf16(synth.text_embeddings(n_txt, cfg.d_model, seed + 2))
+    emb = [torch.tensor(np.concatenate([synth.round_bf16(synth.visual_embeddings(f, patch, wp)), txt])[None],
+                        device=dev) for f in frames]
+    d_frames = [torch.tensor(f[None], device=dev) for f in frames]
+    gm = GpuModel(cfg, seed, max_batch=1, max_seq=320, gain_jitter=0.0, gen_device=dev)
+    ctx, kv = gm.ctx, gm.kv
+    stats = [torch.zeros((nl, 1, n_vis), device=dev) for _ in range(2)]
+    idx = torch.zeros((1, n_vis), dtype=torch.int32, device=dev)
+    order = torch.zeros((1, n_vis), dtype=torch.int32, device=dev)
+    cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+    tok = torch.zeros(1, dtype=torch.int32, device=dev)
+    toks = torch.zeros((1, n_new), dtype=torch.int32, device=dev)
+    dense_flops = FL.prefill_flops(cfg, L, [[]] * nl)
+    rows_out = []
+    for top_k in (50, 100, 150, 200):
+        for tau_task in (0.2, 0.35, 0.5, 0.7):
+            V.vlac_sparse_prefill(ctx, emb[0], 1, n_vis, n_txt, None, None, 1, None, kv, stats[0], None,
+                                  None, tok)
+            reused, pre_ms, step_ms, flops_true, flops_paper = [], [], [], [], []
+            for t in range(1, n_frames):
+                a, b = stats[(t - 1) & 1], stats[t & 1]
+                e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+                e[0].record()
+                V.vlac_select_static(ctx, d_frames[t - 1], d_frames[t], 1, H, H, patch, 249, 250, top_k, a,
+                                     None, tau_task, idx, order, cnt, None, n_vis)
+                e[1].record()
+                V.vlac_sparse_prefill(ctx, emb[t], 1, n_vis, n_txt, order, cnt, n_vis, None, kv, b, None,
+                                      None, tok)
+                e[2].record()
+                V.vlac_decode_action(ctx, 1, L, n_new, tok, kv, toks, None)
+                e[3].record()
+                torch.cuda.synchronize()
+                n = int(cnt.cpu()[0])
+                pos = order[0, :n].cpu().tolist()
+                if t >= 3:                                   # steady state
+                    reused.append(n)
+                    pre_ms.append(e[1].elapsed_time(e[2]))
+                    step_ms.append(e[0].elapsed_time(e[3]))
+                    flops_true.append(FL.prefill_flops(cfg, L, [pos] * nl))
+                    flops_paper.append(FL.paper_step_flops(nl, L, [n] * nl, cfg.d_model, cfg.d_ffn))
+            V.vlac_check(ctx)
+            rows_out.append({"top_k": top_k, "tau_task": tau_task,
+                             "reused_tokens": round(float(np.mean(reused)), 1),
+                             "prefill_ms": round(float(np.median(pre_ms)), 3),
+                             "step_ms": round(float(np.median(step_ms)), 3),
+                             "prefill_tflop_true": round(float(np.mean(flops_true)) / 1e12, 4),
+                             "prefill_tflop_paper_formula": round(float(np.mean(flops_paper)) / 1e12, 4)})
+    # the full recompute of the same stream, for the ratio columns
+    full_ms = []
+    for t in range(1, n_frames):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        e[0].record()
+        V.vlac_sparse_prefill(ctx, emb[t], 1, n_vis, n_txt, None, None, 1, None, kv, stats[0], None, None, tok)
+        e[1].record()
+        torch.cuda.synchronize()
+        full_ms.append(e[0].elapsed_time(e[1]))
+    out = {"metric": "reused_token_sweep", "n_gpus": 1, "dtype": "f16", "data": "synthetic",
+           "config": {"workload": "c3 stream: 7B shape, 256 visual + 32 text tokens, moving 48 px box, "
+                                  "%d frames per setting (steady state: frames 3..%d), layer ratio off"
+                                  % (n_frames, n_frames - 1), "n_layers": nl},
+           "full_recompute": {"prefill_ms": round(float(np.median(full_ms)), 3),
+                              "prefill_tflop_true": round(dense_flops / 1e12, 4),
+                              "prefill_tflop_paper_formula":
+                                  round(nl * FL.paper_layer_flops(L, cfg.d_model, cfg.d_ffn) / 1e12, 4),
+                              "selection_overhead_gflop_paper_formula":
+                                  round(FL.paper_selection_overhead(H, n_txt, n_vis, cfg.d_model) / 1e9, 3)},
+           "sweep": rows_out}
     gm.close()
     print(json.dumps(out))
 
