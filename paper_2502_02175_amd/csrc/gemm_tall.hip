@@ -25,7 +25,10 @@
 //    LDS stores cost 3%), a 256 x 256 tile whose weight tiles are fetched by two waves
 //    each (the second fetch hits L1, but the kernel is 5% slower), a persistent grid that
 //    deals the work items of the actual row count round-robin (2% slower than letting
-//    the hardware dispatch one workgroup per item).
+//    the hardware dispatch one workgroup per item).  The same 8-wave design with one
+//    feature block per wave, up to 8 row tiles and split K, tried for ONE stream's prefill
+//    (33..1023 rows) in place of the 4-wave kernel of gemm.hip, was no faster at any row
+//    count (109 rows: 6.0 vs 5.8 ms per prefill; 248 rows: 8.4 vs 8.2 ms).
 #include "gemm_epi.h"
 
 namespace {
@@ -103,9 +106,12 @@ __device__ __forceinline__ void tall_body(const GemmArgs& a, uint4* lds, int til
   // copies of step i + 1, so "at most 18 loads outstanding" means they have landed; the
   // barrier then makes that true for the copies of all 8 waves, and says that every wave
   // is done with step i - 1, whose buffer takes the tiles of step i + 2.
-#define VLAC_TALL_STEP(i, ph, s0, s1, s2, s3)                \
+  // (In the one or two steps after the last full turn of the loop the count does not hold:
+  // the weight loads of those steps refill slots that nobody reads any more, and the
+  // compiler drops them.  There the wait is for everything.)
+#define VLAC_TALL_STEP(i, ph, s0, s1, s2, s3, WAIT)          \
   {                                                          \
-    asm volatile("s_waitcnt vmcnt(18)" ::: "memory");        \
+    asm volatile(WAIT ::: "memory");                         \
     __syncthreads();                                         \
     copy_x((i) + 2, ((ph) + 2) % 3);                         \
     ktile((i), 0, ph, W[s0]);                                \
@@ -121,13 +127,13 @@ __device__ __forceinline__ void tall_body(const GemmArgs& a, uint4* lds, int til
   asm volatile("s_waitcnt vmcnt(12)" ::: "memory");  // both copies; the 12 weight loads fly on
   int i = 0;
   for (; i + 3 <= KS; i += 3) {
-    VLAC_TALL_STEP(i, 0, 0, 1, 2, 3)
-    VLAC_TALL_STEP(i + 1, 1, 4, 5, 0, 1)
-    VLAC_TALL_STEP(i + 2, 2, 2, 3, 4, 5)
+    VLAC_TALL_STEP(i, 0, 0, 1, 2, 3, "s_waitcnt vmcnt(18)")
+    VLAC_TALL_STEP(i + 1, 1, 4, 5, 0, 1, "s_waitcnt vmcnt(18)")
+    VLAC_TALL_STEP(i + 2, 2, 2, 3, 4, 5, "s_waitcnt vmcnt(18)")
   }
   if (i < KS) {
-    VLAC_TALL_STEP(i, 0, 0, 1, 2, 3)
-    if (i + 1 < KS) VLAC_TALL_STEP(i + 1, 1, 4, 5, 0, 1)
+    VLAC_TALL_STEP(i, 0, 0, 1, 2, 3, "s_waitcnt vmcnt(0)")
+    if (i + 1 < KS) VLAC_TALL_STEP(i + 1, 1, 4, 5, 0, 1, "s_waitcnt vmcnt(0)")
   }
 #undef VLAC_TALL_STEP
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no copy outlives the loop

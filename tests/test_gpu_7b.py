@@ -107,6 +107,11 @@ def test_7b_full_depth_properties():
         np.testing.assert_array_equal(t_same, t_full)
         empty = gm.prefill(e_cur[None], N_VIS, [[]])
         np.testing.assert_array_equal(empty["logits"], full["logits"])
+        # ... and so does any prefix of the static set: 1 to 9 row tiles, one to three row
+        # blocks (every specialisation of the GEMM main loops, their last steps included)
+        for k in (256, 240, 150, 100, 40, 20):
+            part = gm.prefill(e_cur[None], N_VIS, [list(range(k))], want_hidden=False)
+            np.testing.assert_array_equal(part["logits"], full["logits"])
         # a changed frame with reuse: reused rows of the cache keep their bytes, and the
         # result differs from the full recompute of the new frame (how far says nothing
         # with random-init weights, which amplify any perturbation over 32 layers)
