@@ -602,9 +602,14 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, 
     constexpr int MT = 4;
     const int tiles = (n_blocks + 3) / 4;
     a.MB = (rows_cap + MT * 32 - 1) / (MT * 32);
-    // split K until about one workgroup per CU exists for ONE row block (the sparse
-    // prefill usually fills one; a full recompute runs several side by side)
-    int S = (256 + tiles - 1) / tiles;
+    // Split K so that ONE row block (the sparse prefill usually fills one; a full recompute
+    // runs several side by side) gives about one workgroup per CU.  The projections with
+    // a residual round up (their splits cost next to nothing: the row kernel that follows
+    // adds the partial rows); the others round DOWN: their split-K hand-over at the end of
+    // the kernel costs more than leaving a third of the CUs without a workgroup (measured
+    // at the 7B shape, 109 rows: gate/up with 172 tiles 52 us unsplit against 63 us in two
+    // splits; QKV with 96 tiles 42 us in two splits against 52 us in three).
+    int S = epi == EPI_RESID ? (256 + tiles - 1) / tiles : 256 / tiles;
     if (S > a.KS / 4) S = a.KS / 4;
     if (S > 8) S = 8;
     if (S < 1) S = 1;
