@@ -65,6 +65,57 @@ def moving_box_stream(H, W, n_frames, seed, box=48, step=6, noise=0):
     return frames
 
 
+def noisy_scene_stream(H, W, n_frames, seed, patch=14, noise=8, n_distractors=3, lo=16, hi=80,
+                       box=48, step=6):
+    """A stream in the manner of the paper's real-robot setting (Sec. 4.4): a dim static
+    textured background (pixel values in [lo, hi)), sensor noise of +-`noise` on every
+    pixel of every frame, one box of `box` px moving `step` px per frame (the
+    manipulator) and `n_distractors` smaller boxes wandering independently (moving
+    distractors in the background).  With lo > noise no background pixel is clipped.
+
+    Returns (frames uint8 [n_frames, H, W, 3], touched bool [n_frames, n_patches]) where
+    touched[t, i] says that a box overlaps patch i (raster order) in frame t.
+    """
+    rng = np.random.default_rng(seed)
+    gh, gw = H // patch, W // patch
+    bg = rng.integers(lo, hi, size=(H, W, 3), dtype=np.uint8)
+    sizes = [box] + [max(patch, box // 2)] * n_distractors
+    tex = [rng.integers(0, 256, size=(b, b, 3), dtype=np.uint8) for b in sizes]
+    pos = [[int(rng.integers(0, W - b)), int(rng.integers(0, H - b))] for b in sizes]
+    vel = []
+    for k, b in enumerate(sizes):
+        s = step if k == 0 else int(rng.integers(1, step + 1))
+        vel.append([s if rng.random() < 0.5 else -s, 0] if rng.random() < 0.5
+                   else [0, s if rng.random() < 0.5 else -s])
+    frames = np.empty((n_frames, H, W, 3), dtype=np.uint8)
+    touched = np.zeros((n_frames, gh * gw), dtype=bool)
+    for t in range(n_frames):
+        f = bg.copy()
+        for k, b in enumerate(sizes):
+            x, y = pos[k]
+            f[y:y + b, x:x + b] = tex[k]
+            r0, r1 = y // patch, min(gh - 1, (y + b - 1) // patch)
+            c0, c1 = x // patch, min(gw - 1, (x + b - 1) // patch)
+            m = touched[t].reshape(gh, gw)
+            m[r0:r1 + 1, c0:c1 + 1] = True
+        if noise > 0:
+            f = np.clip(f.astype(np.int64) + rng.integers(-noise, noise + 1, size=f.shape),
+                        0, 255).astype(np.uint8)
+        frames[t] = f
+        for k, b in enumerate(sizes):
+            if rng.random() < 0.2:  # change direction now and then
+                s = max(abs(vel[k][0]), abs(vel[k][1]))
+                vel[k] = ([s if rng.random() < 0.5 else -s, 0] if rng.random() < 0.5
+                          else [0, s if rng.random() < 0.5 else -s])
+            for ax, lim in ((0, W - b), (1, H - b)):
+                n = pos[k][ax] + vel[k][ax]
+                if n < 0 or n > lim:
+                    vel[k][ax] = -vel[k][ax]
+                    n = pos[k][ax] + vel[k][ax]
+                pos[k][ax] = n
+    return frames, touched
+
+
 def patch_pixels(frame, patch):
     """[H, W, 3] uint8 -> [N*N, 3*p*p] uint8, patches in raster order."""
     H, W, C = frame.shape

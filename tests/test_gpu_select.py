@@ -57,6 +57,31 @@ def test_select_matches_oracle(gpu, H, patch, n_redraw, k):
             assert order[b] == want          # no relevance: reuse order is the index order
 
 
+@pytest.mark.parametrize("noise,lo,hi", [(8, 16, 80), (20, 8, 64), (2, 32, 224)])
+def test_select_on_noisy_streams_with_distractors(gpu, noise, lo, hi):
+    """Camera-noise streams with moving distractors at the noise-tolerant threshold
+    17/20 and at the simulator's 249/250, with and without the top-k cut and the
+    task-relevance filter: index sets and reuse order bit for bit."""
+    B, H, p, n_frames, nl = 4, 224, 14, 4, gpu["n_layers"]
+    streams = [synth.noisy_scene_stream(H, H, n_frames, seed=90 + b, patch=p, noise=noise, lo=lo, hi=hi,
+                                        n_distractors=b)[0] for b in range(B)]
+    rng = np.random.default_rng(noise)
+    attn = (rng.random((nl, B, 256)) ** 3).astype(np.float32)
+    for t in range(1, n_frames):
+        prev = np.stack([s[t - 1] for s in streams])
+        cur = np.stack([s[t] for s in streams])
+        for tn, td in ((17, 20), (249, 250)):
+            for k in (100, 256):
+                idx, order, _ = run_select(gpu, prev, cur, p, tn, td, k)
+                for b in range(B):
+                    assert idx[b] == O.select_static(prev[b], cur[b], p, tn, td, k), (t, b, tn, k)
+            idx, order, rel = run_select(gpu, prev, cur, p, tn, td, 180, attn, None, 0.4)
+            for b in range(B):
+                p_static = O.select_static(prev[b], cur[b], p, tn, td, 180)
+                want, want_order = O.filter_task_relevant(p_static, O.task_relevance(attn[:, b]), 0.4)
+                assert idx[b] == want and order[b] == want_order
+
+
 def test_select_ties_zero_patches_and_extremes(gpu):
     rng = np.random.default_rng(3)
     H, p = 56, 14
