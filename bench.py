@@ -54,11 +54,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c3n", "c4", "c5"],
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c3n", "c4", "c5", "oft"],
                     help="c2: the benchmark's workload (default); c3: a 64-frame stream with the "
                          "task-relevance filter and layer-adaptive reuse on; c3n: the same on a noisy "
                          "scene with moving distractors at tau = 17/20; c4 / c5: the batched-stream "
-                         "shapes, where the recomputed-row GEMMs are bound by the matrix cores")
+                         "shapes, where the recomputed-row GEMMs are bound by the matrix cores; oft: two "
+                         "camera views and a chunk of 56 action rows read off one pass (no decode passes)")
     ap.add_argument("--sweep", action="store_true",
                     help="reused-token sweep on a synthetic frame stream (top-k x tau_task), with the "
                          "paper's operation estimate beside the true count; prints its own JSON line")
@@ -89,6 +90,8 @@ def main():
 
     if args.workload in ("c3", "c3n"):
         return stream(args, V, GpuModel, np, torch, synth, dev)
+    if args.workload == "oft":
+        return two_views_chunk(args, V, GpuModel, np, torch, synth, dev)
     if args.workload != "c2":
         return batched(args, V, GpuModel, np, torch, synth, dev)
     if args.sweep:
@@ -485,6 +488,78 @@ def stream(args, V, GpuModel, np, torch, synth, dev):
                      "reused_per_layer_mean": round(float(r[:, 1].mean()), 1),
                      "recomputed_rows_per_layer_mean": round(float(rows), 1), "gain_k": round(gain, 3)},
            "prefill_speedup_vs_full": round(float(np.median(full)) / med(3), 3)}
+    gm.close()
+    print(json.dumps(out))
+
+
+def two_views_chunk(args, V, GpuModel, np, torch, synth, dev):
+    """The parallel-decoding shape of the paper's third model (Sec. 4.2, 4.3): two camera
+    views per step (a fixed third-person view that is mostly static, a wrist view that is
+    not) = 512 visual tokens, 32 prompt tokens and a chunk of 8 actions x 7 dimensions =
+    56 placeholder rows whose final hidden states an action head reads: ONE pass per control
+    step and no sequential decode passes.  Alg. 1 over both views at once (the views stacked
+    into one 448 x 224 frame), top-k 100, tau_task 0.5 (that model's defaults in the
+    sensitivity tables), layer ratio off.  7B layer shape, random-init weights, causal
+    attention (shape only).  Steady state = frames 4..23, medians."""
+    cfg = synth.CONFIGS["7b"]
+    if args.layers:
+        cfg = cfg.with_layers(args.layers)
+    H, patch, n_vis, n_txt, n_act, seed, top_k, tau_task = 224, 14, 512, 32, 56, 0, 100, 0.5
+    L_t = n_txt + n_act
+    L, nl, n_frames, warm = n_vis + L_t, cfg.n_layers, 24, 4
+    frames = synth.two_view_stream(H, H, n_frames, seed=seed + 7)
+    wp = synth.projection_matrix(cfg.d_model, patch, seed + 1)
+    tail = synth.round_bf16(synth.text_embeddings(L_t, cfg.d_model, seed + 2))
+    emb = [torch.tensor(np.concatenate([synth.round_bf16(synth.visual_embeddings(f, patch, wp)), tail])[None],
+                        device=dev) for f in frames]
+    d_frames = [torch.tensor(f[None], device=dev) for f in frames]
+    gm = GpuModel(cfg, seed, max_batch=1, max_seq=608, gain_jitter=0.0, gen_device=dev)
+    ctx, kv = gm.ctx, gm.kv
+    stats = [torch.zeros((nl, 1, n_vis), device=dev) for _ in range(2)]
+    i32 = dict(dtype=torch.int32, device=dev)
+    idx, order = torch.zeros((1, n_vis), **i32), torch.zeros((1, n_vis), **i32)
+    cnt, tok = torch.zeros(1, **i32), torch.zeros(1, **i32)
+    hidden = torch.zeros((1, L, cfg.d_model), device=dev)
+    V.vlac_sparse_prefill(ctx, emb[0], 1, n_vis, L_t, None, None, 1, None, kv, stats[0], hidden, None, tok)
+    rec = []
+    for t in range(1, n_frames):
+        a, b = stats[(t - 1) & 1], stats[t & 1]
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record()
+        V.vlac_select_static(ctx, d_frames[t - 1], d_frames[t], 1, 2 * H, H, patch, 249, 250, top_k, a,
+                             None, tau_task, idx, order, cnt, None, n_vis)
+        e[1].record()
+        V.vlac_sparse_prefill(ctx, emb[t], 1, n_vis, L_t, order, cnt, n_vis, None, kv, b, hidden, None, tok)
+        e[2].record()
+        torch.cuda.synchronize()
+        if t >= warm:
+            rec.append((int(cnt.cpu()[0]), e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2]),
+                        e[0].elapsed_time(e[2])))
+    V.vlac_check(ctx)
+    full = []
+    for t in range(warm, warm + 8):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        e[0].record()
+        V.vlac_sparse_prefill(ctx, emb[t], 1, n_vis, L_t, None, None, 1, None, kv, stats[0], hidden, None, tok)
+        e[1].record()
+        torch.cuda.synchronize()
+        full.append(e[0].elapsed_time(e[1]))
+    r = np.array(rec)
+    med = lambda j: float(np.median(r[:, j]))
+    rows = L - r[:, 0].mean()
+    out = {"metric": "recomputed_token_prefill_tok_per_s", "value": round(rows / (med(2) * 1e-3), 1),
+           "unit": "tokens/s", "n_gpus": 1, "steps": len(rec), "warmup": warm, "ms_per_step": round(med(3), 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+           "data": "synthetic",
+           "config": {"workload": "two views + action chunk: 7B shape, 2 x 256 visual + 32 prompt + 56 action "
+                                  "rows in one pass, fixed view with a moving box over a panning wrist view, "
+                                  "top-k %d, tau_task %.2f, no decode passes" % (top_k, tau_task),
+                      "n_layers": nl},
+           "phases_ms": {"select": round(med(1), 4), "sparse_pass": round(med(2), 4),
+                         "full_pass": round(float(np.median(full)), 4)},
+           "reuse": {"reused_tokens_mean": round(float(r[:, 0].mean()), 1),
+                     "recomputed_rows_mean": round(float(rows), 1)},
+           "pass_speedup_vs_full": round(float(np.median(full)) / med(2), 3)}
     gm.close()
     print(json.dumps(out))
 

@@ -116,6 +116,29 @@ def noisy_scene_stream(H, W, n_frames, seed, patch=14, noise=8, n_distractors=3,
     return frames, touched
 
 
+def two_view_stream(H, W, n_frames, seed, pan=5):
+    """Two camera views per step, stacked into one frame of 2H x W pixels (so that the
+    patches in raster order are view 0's followed by view 1's): on top a fixed
+    third-person view (`moving_box_stream`: mostly static), below it a wrist-camera view
+    that moves with the arm: a window panning `pan` pixels per frame over a larger
+    random texture, where next to nothing stays in place (Sec. 4.3 on dynamic viewpoints).
+
+    Returns uint8 [n_frames, 2H, W, 3].
+    """
+    rng = np.random.default_rng(seed + 1000)
+    top = moving_box_stream(H, W, n_frames, seed)
+    canvas = rng.integers(0, 256, size=(H + 2 * pan * n_frames + 2, W + 2 * pan * n_frames + 2, 3),
+                          dtype=np.uint8)
+    x = y = pan * n_frames
+    frames = np.empty((n_frames, 2 * H, W, 3), dtype=np.uint8)
+    for t in range(n_frames):
+        frames[t, :H] = top[t]
+        frames[t, H:] = canvas[y:y + H, x:x + W]
+        dx, dy = [(pan, 0), (-pan, 0), (0, pan), (0, -pan)][int(rng.integers(0, 4))]
+        x, y = x + dx, y + dy
+    return frames
+
+
 def patch_pixels(frame, patch):
     """[H, W, 3] uint8 -> [N*N, 3*p*p] uint8, patches in raster order."""
     H, W, C = frame.shape

@@ -296,3 +296,46 @@ def test_frame_stream_with_filter_and_layer_adaptive_reuse(scene):
             assert all(0.80 * N_VIS <= n <= 0.95 * N_VIS for n in n_static_seen), n_static_seen
     finally:
         gm.close()
+
+
+def test_two_views_and_a_chunk_of_action_rows_in_one_pass():
+    """The parallel-decoding shape (an action chunk read off ONE pass instead of 7
+    sequential decode passes; two camera views): 512 visual tokens from two stacked
+    224 x 224 views (the fixed one mostly static, the wrist view not), 32 prompt tokens
+    and 56 action placeholder rows (8 actions x 7 dimensions), which are recomputed at
+    every step like the prompt.  7B layer shape, 2 layers; the final hidden states of
+    the 56 action rows (what an action head would read) against the oracle.  Attention
+    stays causal here (shape only)."""
+    TOL = TOLS["f16"]
+    cfg = CFG.with_layers(2)
+    n_vis, n_txt, n_act, k = 512, 32, 56, 100
+    L_ = n_vis + n_txt + n_act
+    frames = synth.two_view_stream(H, H, 3, seed=41)
+    wp = synth.projection_matrix(cfg.d_model, PATCH, 42)
+    tail = synth.round_bf16(synth.text_embeddings(n_txt + n_act, cfg.d_model, 43))
+    emb = [np.concatenate([synth.round_bf16(synth.visual_embeddings(f, PATCH, wp)), tail]) for f in frames]
+    om = oracle_model(cfg, seed=6, gain_jitter=0.1)
+    gm = GpuModel(cfg, seed=6, max_batch=1, max_seq=608, gain_jitter=0.1)
+    try:
+        cache = O.new_cache(cfg, 608)
+        want = O.dense_forward(om, emb[0], n_vis, cache)
+        got = gm.prefill(emb[0][None], n_vis)
+        assert np.abs(got["hidden"][0] - want["hidden"]).max() <= TOL
+        for t in (1, 2):
+            stats = want["attn_mean"].astype(np.float32)
+            p_final, order, _, _ = O.plan_step(frames[t - 1], frames[t], PATCH, 249, 250, k, stats, 0.5, 1.0)
+            sel = gm.select(frames[t - 1][None], frames[t][None], PATCH, 249, 250, k, stats[:, None], 0.5)
+            assert sel["idx"][0] == p_final and sel["order"][0] == order
+            assert 0 < len(p_final) <= k and max(p_final) < n_vis // 2     # all from the fixed view
+            want = O.sparse_forward(om, emb[t], n_vis, cache, [order] * cfg.n_layers)
+            got = gm.prefill(emb[t][None], n_vis, [order])
+            alive = ~np.isnan(want["hidden"][:, 0])
+            assert alive[-n_act:].all() and alive.sum() == L_ - len(p_final)
+            e_h = np.abs(got["hidden"][0][alive] - want["hidden"][alive]).max()
+            e_a = np.abs(got["hidden"][0][-n_act:] - want["hidden"][-n_act:]).max()
+            print("\nstep %d: %d reused, max-abs hidden %.4g (action rows %.4g)" % (t, len(p_final), e_h, e_a))
+            assert e_h <= TOL
+            assert np.all(np.isnan(got["hidden"][0][~alive]))
+            np.testing.assert_allclose(got["attn_mean"][:, 0], want["attn_mean"], atol=1e-4, rtol=2e-2)
+    finally:
+        gm.close()

@@ -82,6 +82,21 @@ def test_select_on_noisy_streams_with_distractors(gpu, noise, lo, hi):
                 assert idx[b] == want and order[b] == want_order
 
 
+def test_select_two_stacked_views(gpu):
+    """Two camera views stacked into one 448 x 224 frame (512 patches; H != W): a fixed
+    view that is mostly static over a wrist view where next to nothing is."""
+    B, H, p = 3, 224, 14
+    streams = [synth.two_view_stream(H, H, 4, seed=70 + b) for b in range(B)]
+    for t in range(1, 4):
+        prev = np.stack([s[t - 1] for s in streams])
+        cur = np.stack([s[t] for s in streams])
+        for k in (100, 512):
+            idx, order, _ = run_select(gpu, prev, cur, p, 249, 250, k)
+            for b in range(B):
+                assert idx[b] == O.select_static(prev[b], cur[b], p, 249, 250, k)
+                assert len(idx[b]) == min(k, len(O.select_static(prev[b], cur[b], p, 249, 250, 512)))
+
+
 def test_select_ties_zero_patches_and_extremes(gpu):
     rng = np.random.default_rng(3)
     H, p = 56, 14

@@ -245,3 +245,27 @@ def test_plan_step_no_stats():
     prev, cur, redrawn = synth.frame_pair(112, 112, 14, 16, seed=0)
     p_final, order, per_layer, alpha = O.plan_step(prev, cur, 14, 249, 250, 32, None, 0.5, 1.0)
     assert per_layer is None and alpha is None and order == p_final and len(p_final) == 32
+
+
+# ---------------- two camera views as one stacked frame ----------------
+
+def test_two_stacked_views_select_like_each_view_alone():
+    """The patch test is local to a patch, so two views stacked into one 2H x W frame
+    (patches in raster order = view 0's, then view 1's) select what each view selects on
+    its own, indices of the second shifted by the first view's patch count; with a
+    top-k smaller than that, the k most similar of BOTH views are kept."""
+    H, p = 112, 14
+    n = (H // p) ** 2
+    fr = synth.two_view_stream(H, H, 5, seed=11)
+    assert fr.shape == (5, 2 * H, H, 3)
+    for t in range(1, 5):
+        both = O.select_static(fr[t - 1], fr[t], p, 249, 250, 2 * n)
+        top = O.select_static(fr[t - 1][:H], fr[t][:H], p, 249, 250, n)
+        bot = O.select_static(fr[t - 1][H:], fr[t][H:], p, 249, 250, n)
+        assert both == top + [n + i for i in bot]
+        assert len(top) > n // 2 and len(bot) < n // 8          # fixed view static, wrist view not
+        terms = O.patch_terms(fr[t - 1], fr[t], p)
+        sims = [Fraction(int(d) ** 2, int(a) * int(b)) for d, a, b in terms]
+        k = 20
+        want = sorted(sorted(both, key=lambda i: (-sims[i], i))[:k])
+        assert O.select_static(fr[t - 1], fr[t], p, 249, 250, k) == want
