@@ -200,23 +200,25 @@ def main():
         V.vlac_profile_select(ctx, kind)
         sparse_step()
         torch.cuda.synchronize()
-        tot, n = V.vlac_profile_read(ctx)
+        tot, mark, n = V.vlac_profile_read2(ctx)
         if n:
             epi, cls = kind % 4, kind // 4
             rows = 1 if cls == 0 else n_rows
             kernels[kind] = {"name": "gemm_rows<%s> %s" % (KIND_NAMES[epi], CLASS_NAMES[cls]),
-                             "launches_per_step": n, "avg_us": tot / n * 1e3,
+                             "launches_per_step": n, "avg_us": tot / n * 1e3, "marker_us": mark / n * 1e3,
                              "ms_per_step": tot, "bytes": gemm_bytes(cfg, epi, rows)}
     V.vlac_profile_select(ctx, -1)
-    # an event bracket with nothing inside: what the two markers themselves add to a bracket
-    brackets = []
-    for _ in range(64):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        b.record()
-        brackets.append((a, b))
+    # What a bracket adds to the kernel inside it: measured with a kernel that times itself
+    # (it spins on the GPU's wall clock for 20 us and stores what it saw), bracketed the same
+    # way on the same stream.  (The marker that follows every bracket reads about 5 us from
+    # its predecessor: markers retire more slowly behind markers than kernels do.)
+    # rocprofv3's duration of that kernel is 0.6 us more than its own reading (its wave
+    # has to be launched and retired: 20.68 against 20.05 us), and a kernel's duration here
+    # means what the profiler means.
     torch.cuda.synchronize()
-    ev_overhead_us = float(np.median([a.elapsed_time(b) for a, b in brackets])) * 1e3
+    ev_overhead_us = V.vlac_profile_bracket_cost(ctx) - 0.6
+    n_all = sum(k["launches_per_step"] for k in kernels.values())
+    marker_us = sum(k["marker_us"] * k["launches_per_step"] for k in kernels.values()) / max(n_all, 1)
     # the dominant kernel: most time per step once the brackets' own share is taken out
     dom = max(kernels, key=lambda k: (kernels[k]["avg_us"] - ev_overhead_us) * kernels[k]["launches_per_step"])
     kd = kernels[dom]
@@ -229,6 +231,7 @@ def main():
                 "bytes_per_launch": kd["bytes"], "avg_launch_us": round(dur_us, 2),
                 "avg_launch_us_raw_events": round(kd["avg_us"], 2),
                 "event_bracket_overhead_us": round(ev_overhead_us, 2),
+                "marker_after_marker_us": round(marker_us, 2),
                 "launches_per_step": kd["launches_per_step"]}
 
     weight_bytes = 2 * nl * (cfg.d_model * (cfg.q_dim + 2 * cfg.kv_dim) + cfg.q_dim * cfg.d_model +

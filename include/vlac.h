@@ -119,9 +119,20 @@ int vlac_check(vlac_ctx* ctx, void* stream);
  * class 0: at most 32 rows (decode, head), 1: more (prefill).  kind -1 switches it off.
  * vlac_profile_read waits for the recorded launches and returns their summed
  * elapsed time and their number, then starts counting afresh (at most 2048
- * launches are recorded between reads). */
+ * launches are recorded between reads).  A bracket measures more than the kernel (the
+ * markers are queue packets of their own), so every bracket is followed by one more
+ * marker, and vlac_profile_read2 also returns the summed time from the closing marker
+ * to that one (marker_ms, may be NULL): what a marker costs right behind a marker on
+ * the same busy stream. */
 int vlac_profile_select(vlac_ctx* ctx, int kind);
 int vlac_profile_read(vlac_ctx* ctx, double* total_ms, int* launches);
+int vlac_profile_read2(vlac_ctx* ctx, double* total_ms, double* marker_ms, int* launches);
+/* What an event bracket adds to the kernel inside it, in microseconds: brackets 40
+ * launches of a one-wave kernel that spins on the GPU's constant-rate wall clock for 20 us
+ * and stores the time it saw itself run, waits for `stream`, and returns the mean of
+ * (bracket - the kernel's own time) over the last 32.  Uses the split-K workspace: call it
+ * while nothing else of this context runs. */
+int vlac_profile_bracket_cost(vlac_ctx* ctx, void* stream, double* cost_us);
 
 /* Alg. 1 (Sec. 3.2 Eq. sim, Eq. topk; Sec. 3.3 Eq. ptask, Eq. pfinal).
  *

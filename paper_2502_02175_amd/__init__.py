@@ -4,7 +4,8 @@ from .binding import (VlacError, ModelCfg, LayerW, OPERAND_BF16, OPERAND_F16, li
                       vlac_create, vlac_destroy, vlac_set_layer_weights, vlac_set_head_weights,
                       vlac_kv_cache_bytes, vlac_reset_stream, vlac_check, vlac_select_static,
                       vlac_layer_ratio, vlac_sparse_prefill, vlac_decode_action,
-                      vlac_last_hip_error, vlac_profile_select, vlac_profile_read)
+                      vlac_last_hip_error, vlac_profile_select, vlac_profile_read,
+                      vlac_profile_read2, vlac_profile_bracket_cost)
 
 __all__ = [n for n in dir() if n.startswith("vlac_")] + [
     "VlacError", "ModelCfg", "LayerW", "OPERAND_BF16", "OPERAND_F16", "lib", "lib_path", "status_string"]

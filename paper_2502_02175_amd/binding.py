@@ -61,6 +61,8 @@ def lib():
         L.vlac_check.argtypes = [vp, vp]
         L.vlac_profile_select.argtypes = [vp, i32]
         L.vlac_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
+        L.vlac_profile_read2.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(i32)]
+        L.vlac_profile_bracket_cost.argtypes = [vp, vp, C.POINTER(C.c_double)]
         L.vlac_select_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, f32,
                                          vp, vp, vp, vp, i32, vp]
         L.vlac_layer_ratio.argtypes = [vp, vp, i32, i32, f32, vp, vp, vp, vp]
@@ -68,7 +70,8 @@ def lib():
         L.vlac_decode_action.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp]
         for name in ("vlac_create", "vlac_destroy", "vlac_last_hip_error", "vlac_set_layer_weights",
                      "vlac_set_head_weights", "vlac_reset_stream", "vlac_check",
-                     "vlac_profile_select", "vlac_profile_read",
+                     "vlac_profile_select", "vlac_profile_read", "vlac_profile_read2",
+                     "vlac_profile_bracket_cost",
                      "vlac_select_static", "vlac_layer_ratio", "vlac_sparse_prefill",
                      "vlac_decode_action"):
             getattr(L, name).restype = i32
@@ -174,6 +177,20 @@ def vlac_profile_read(ctx, check=True):
     ms, n = C.c_double(), C.c_int()
     _ret(lib().vlac_profile_read(ctx, C.byref(ms), C.byref(n)), "vlac_profile_read", check)
     return ms.value, n.value
+
+
+def vlac_profile_bracket_cost(ctx, stream=None, check=True):
+    """Microseconds that an event bracket adds to the kernel inside it."""
+    us = C.c_double()
+    _ret(lib().vlac_profile_bracket_cost(ctx, _stream(stream), C.byref(us)), "vlac_profile_bracket_cost", check)
+    return us.value
+
+
+def vlac_profile_read2(ctx, check=True):
+    """Returns (total_ms, marker_ms, launches)."""
+    ms, mk, n = C.c_double(), C.c_double(), C.c_int()
+    _ret(lib().vlac_profile_read2(ctx, C.byref(ms), C.byref(mk), C.byref(n)), "vlac_profile_read2", check)
+    return ms.value, mk.value, n.value
 
 
 def vlac_select_static(ctx, frame_prev, frame_cur, B, H, W, patch, tau_num, tau_den, top_k,

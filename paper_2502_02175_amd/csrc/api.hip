@@ -11,6 +11,17 @@
 
 namespace {
 
+// A kernel that knows how long it ran: one wave reads the constant-rate wall clock (100
+// MHz) until `ticks` have passed (or a bounded number of reads, so that it ends whatever
+// the clock does) and stores the ticks it saw.  The yardstick for what an event bracket
+// adds to the kernel inside it (vlac_profile_bracket_cost).
+__global__ void spin_kernel(unsigned long long ticks, unsigned long long* out) {
+  const unsigned long long t0 = wall_clock64();
+  unsigned long long t = t0;
+  for (int it = 0; it < (1 << 20) && t - t0 < ticks; ++it) t = wall_clock64();
+  if (threadIdx.x == 0) *out = t - t0;
+}
+
 template <class T>
 hipError_t dalloc(T** p, size_t n) {
   *p = nullptr;
@@ -56,8 +67,9 @@ void free_all(vlac_ctx* c) {
   for (int i = 0; i < c->prof_cap; ++i) {
     if (c->prof_start) (void)hipEventDestroy(c->prof_start[i]);
     if (c->prof_stop) (void)hipEventDestroy(c->prof_stop[i]);
+    if (c->prof_mark) (void)hipEventDestroy(c->prof_mark[i]);
   }
-  free(c->prof_start); free(c->prof_stop);
+  free(c->prof_start); free(c->prof_stop); free(c->prof_mark);
   free(c->layer_set); free(c->filled); free(c->was_reset);
   free(c);
 }
@@ -266,10 +278,12 @@ int vlac_profile_select(vlac_ctx* ctx, int kind) {
     const int cap = 2048;
     ctx->prof_start = (hipEvent_t*)calloc(cap, sizeof(hipEvent_t));
     ctx->prof_stop = (hipEvent_t*)calloc(cap, sizeof(hipEvent_t));
-    if (!ctx->prof_start || !ctx->prof_stop) return VLAC_E_NOMEM;
+    ctx->prof_mark = (hipEvent_t*)calloc(cap, sizeof(hipEvent_t));
+    if (!ctx->prof_start || !ctx->prof_stop || !ctx->prof_mark) return VLAC_E_NOMEM;
     for (int i = 0; i < cap; ++i) {
       VLAC_HIP(hipEventCreate(&ctx->prof_start[i]));
       VLAC_HIP(hipEventCreate(&ctx->prof_stop[i]));
+      VLAC_HIP(hipEventCreate(&ctx->prof_mark[i]));
       ctx->prof_cap = i + 1;
     }
   }
@@ -278,19 +292,58 @@ int vlac_profile_select(vlac_ctx* ctx, int kind) {
   return VLAC_OK;
 }
 
-int vlac_profile_read(vlac_ctx* ctx, double* total_ms, int* launches) {
+int vlac_profile_read2(vlac_ctx* ctx, double* total_ms, double* marker_ms, int* launches) {
   if (!ctx || !total_ms || !launches) return VLAC_E_NULL;
-  double tot = 0;
+  double tot = 0, mark = 0;
   for (int i = 0; i < ctx->prof_n; ++i) {
-    VLAC_HIP(hipEventSynchronize(ctx->prof_stop[i]));
+    VLAC_HIP(hipEventSynchronize(ctx->prof_mark[i]));
     float ms = 0.f;
     VLAC_HIP(hipEventElapsedTime(&ms, ctx->prof_start[i], ctx->prof_stop[i]));
     tot += ms;
+    VLAC_HIP(hipEventElapsedTime(&ms, ctx->prof_stop[i], ctx->prof_mark[i]));
+    mark += ms;
   }
   *total_ms = tot;
+  if (marker_ms) *marker_ms = mark;
   *launches = ctx->prof_n;
   ctx->prof_n = 0;
   return VLAC_OK;
+}
+
+int vlac_profile_read(vlac_ctx* ctx, double* total_ms, int* launches) {
+  return vlac_profile_read2(ctx, total_ms, nullptr, launches);
+}
+
+int vlac_profile_bracket_cost(vlac_ctx* ctx, void* stream, double* cost_us) {
+  if (!ctx || !cost_us) return VLAC_E_NULL;
+  constexpr int N = 40, SKIP = 8;
+  hipStream_t st = (hipStream_t)stream;
+  hipEvent_t ev[2 * N];
+  int made = 0, rc = VLAC_OK;
+  unsigned long long self[N];
+  unsigned long long* d_self = (unsigned long long*)ctx->partial;  // idle between launches
+  for (; made < 2 * N; ++made)
+    if (hipEventCreate(&ev[made]) != hipSuccess) { rc = VLAC_E_HIP; break; }
+  if (rc == VLAC_OK) {
+    for (int i = 0; i < N; ++i) {
+      (void)hipEventRecord(ev[2 * i], st);
+      hipLaunchKernelGGL(spin_kernel, dim3(1), dim3(64), 0, st, 2000ull, d_self + i);  // 20 us
+      (void)hipEventRecord(ev[2 * i + 1], st);
+    }
+    if (hipMemcpyAsync(self, d_self, sizeof(self), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) rc = VLAC_E_HIP;
+  }
+  if (rc == VLAC_OK) {
+    double sum = 0;
+    for (int i = SKIP; i < N; ++i) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]) != hipSuccess) { rc = VLAC_E_HIP; break; }
+      sum += (double)ms * 1e3 - (double)self[i] * 0.01;  // the wall clock counts at 100 MHz
+    }
+    *cost_us = sum / (N - SKIP);
+  }
+  for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+  return rc;
 }
 
 int vlac_check(vlac_ctx* ctx, void* stream) {

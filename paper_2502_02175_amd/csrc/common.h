@@ -136,7 +136,7 @@ struct vlac_ctx {
   uint8_t* was_reset;
   // per-launch timing of one GEMM class (vlac_profile_select)
   int prof_kind, prof_n, prof_cap;
-  hipEvent_t *prof_start, *prof_stop;
+  hipEvent_t *prof_start, *prof_stop, *prof_mark;
 };
 
 #define VLAC_HIP(call)                         \

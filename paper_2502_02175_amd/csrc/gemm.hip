@@ -625,6 +625,9 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, 
     if (c->f16) launch_mt<MT, true>(epi, a, grid, st);
     else launch_mt<MT, false>(epi, a, grid, st);
   }
-  if (timed) (void)hipEventRecord(c->prof_stop[c->prof_n++], st);
+  if (timed) {
+    (void)hipEventRecord(c->prof_stop[c->prof_n], st);
+    (void)hipEventRecord(c->prof_mark[c->prof_n++], st);  // marker after marker: the bracket's own cost
+  }
   return a.S;
 }
