@@ -234,6 +234,21 @@ def main():
                 "marker_after_marker_us": round(marker_us, 2),
                 "launches_per_step": kd["launches_per_step"]}
 
+    # The front end (not part of the timed step: the step takes the embeddings as inputs, as
+    # the method leaves the vision encoder alone): the patch -> embedding projection for the
+    # 77 recomputed patches only, and for all 256.
+    d_wp = t(synth.round_bf16(wp)).to(torch.bfloat16)
+    d_emb = torch.zeros((1, L, cfg.d_model), device=dev)
+    front = {}
+    for name, ro, rc in (("embed_recomputed_patches_us", order, cnt), ("embed_all_patches_us", None, None)):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+        for a, b in ev:
+            a.record()
+            V.vlac_embed_patches(ctx, d_cur, 1, H, H, patch, d_wp, ro, rc, top_k, None, d_emb, L)
+            b.record()
+        torch.cuda.synchronize()
+        front[name] = round(float(np.median([a.elapsed_time(b) for a, b in ev[4:]])) * 1e3, 1)
+
     weight_bytes = 2 * nl * (cfg.d_model * (cfg.q_dim + 2 * cfg.kv_dim) + cfg.q_dim * cfg.d_model +
                              3 * cfg.d_model * cfg.d_ffn)
     head_bytes = 2 * cfg.vocab * cfg.d_model
@@ -264,6 +279,7 @@ def main():
                                 "GBps": round(v["bytes"] / (v["avg_us"] * 1e-6) / 1e9, 1)}
                     for v in kernels.values()},
         "roofline": roofline,
+        "front_end": front,
         "paper_context": "paper: up to 1.7x latency speedup, ~15% control frequency, one RTX 4090, bf16",
     }
     if not args.no_cpu_baseline:

@@ -163,6 +163,23 @@ int vlac_select_static(vlac_ctx* ctx, const uint8_t* frame_prev, const uint8_t* 
                        int32_t* out_idx, int32_t* out_order, int32_t* out_count,
                        float* out_relevance, int stride, void* stream);
 
+/* Front end for the visual tokens (beyond Alg. 1, in its spirit: a token whose K/V are
+ * reused at the first decoder layer, Alg. 2, needs no input embedding either).  The
+ * embedding of patch i of frame_cur is the fixed linear map
+ *   e_i = (pixels_i / 127.5 - 1) . w_proj,
+ * pixels_i = the patch as [patch rows][patch cols][3] bytes, w_proj: device bf16
+ * [3 patch^2, d_model] row-major (the stand-in for the vision encoder, which the method
+ * leaves alone).  It is computed, in fp32, for every patch EXCEPT the first
+ * m = min(reuse_count[b], layer_count[b, 0]) entries of reuse_order[b, :] (the rows that
+ * vlac_sparse_prefill with the same lists recomputes at layer 0), and written to
+ * embeds[b, i, :]; rows of the excepted patches and rows >= L_v are left untouched.
+ * reuse_order / reuse_count both NULL: every patch.  layer_count may be NULL.
+ * frame_cur: device uint8 [B, H, W, 3]; embeds: device fp32 [B, L, d_model], L >= L_v;
+ * H, W multiples of patch, L_v = (H/patch)(W/patch) <= 4096, patch <= 26. */
+int vlac_embed_patches(vlac_ctx* ctx, const uint8_t* frame_cur, int B, int H, int W, int patch,
+                       const void* w_proj, const int32_t* reuse_order, const int32_t* reuse_count,
+                       int stride, const int32_t* layer_count, float* embeds, int L, void* stream);
+
 /* Sec. 3.4, Eq. reuse_ratio: per stream, entropy E^l of attn_mean[l, b, :]
  * normalised over the vision tokens, R^l = (E^{l-1} - E^l) / E^{l-1} (R^1 = 0;
  * 0 when E^{l-1} = 0), alpha^l = clamp(gain_k * sum_{j<=l} R^j, 0, 1), made

@@ -104,6 +104,28 @@ def select_static(frame_prev, frame_cur, patch, tau_num, tau_den, top_k):
 # --------------------------------------------------------------------------
 
 
+def embed_patches(frame, patch, w_proj, skip=()):
+    """Front end for the visual tokens, for the patches that are recomputed only (the
+    token reuse of Sec. 3.2 / Alg. 2 carried one step further forward: a token whose K/V
+    are reused at the first layer needs no embedding).  The embedding is the fixed linear
+    map that stands in for the vision encoder: e_i = (pixels_i / 127.5 - 1) . W with
+    pixels_i the patch as [rows][cols][channel] bytes and W of shape [3 p^2, d].
+    Returns fp64 [n_patches, d]; rows of patches in `skip` are NaN."""
+    H, Wd, C = frame.shape
+    gh, gw = H // patch, Wd // patch
+    w = np.asarray(w_proj, dtype=np.float64)
+    out = np.full((gh * gw, w.shape[1]), np.nan)
+    skip = set(int(i) for i in skip)
+    for r in range(gh):
+        for c in range(gw):
+            i = r * gw + c
+            if i in skip:
+                continue
+            pix = frame[r * patch:(r + 1) * patch, c * patch:(c + 1) * patch, :].astype(np.float64)
+            out[i] = (pix.reshape(-1) / 127.5 - 1.0) @ w
+    return out
+
+
 def task_relevance(attn_mean, layer_mask=None):
     """S_task-relevance: the mean over the selected layers of A^l_avg.
 

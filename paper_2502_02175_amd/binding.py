@@ -65,6 +65,7 @@ def lib():
         L.vlac_profile_bracket_cost.argtypes = [vp, vp, C.POINTER(C.c_double)]
         L.vlac_select_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, f32,
                                          vp, vp, vp, vp, i32, vp]
+        L.vlac_embed_patches.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, i32, vp]
         L.vlac_layer_ratio.argtypes = [vp, vp, i32, i32, f32, vp, vp, vp, vp]
         L.vlac_sparse_prefill.argtypes = [vp, vp, i32, i32, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.vlac_decode_action.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp]
@@ -72,7 +73,7 @@ def lib():
                      "vlac_set_head_weights", "vlac_reset_stream", "vlac_check",
                      "vlac_profile_select", "vlac_profile_read", "vlac_profile_read2",
                      "vlac_profile_bracket_cost",
-                     "vlac_select_static", "vlac_layer_ratio", "vlac_sparse_prefill",
+                     "vlac_select_static", "vlac_embed_patches", "vlac_layer_ratio", "vlac_sparse_prefill",
                      "vlac_decode_action"):
             getattr(L, name).restype = i32
         _LIB = L
@@ -208,6 +209,18 @@ def vlac_select_static(ctx, frame_prev, frame_cur, B, H, W, patch, tau_num, tau_
         _ptr(out_count, torch.int32, "out_count"), _ptr(out_relevance, torch.float32, "out_relevance"),
         stride, _stream(stream))
     return _ret(st, "vlac_select_static", check)
+
+
+def vlac_embed_patches(ctx, frame_cur, B, H, W, patch, w_proj, reuse_order, reuse_count, stride,
+                       layer_count, embeds, L, stream=None, check=True):
+    import torch
+    i32 = torch.int32
+    st = lib().vlac_embed_patches(
+        ctx, _ptr(frame_cur, torch.uint8, "frame_cur"), B, H, W, patch,
+        _ptr(w_proj, torch.bfloat16, "w_proj"), _ptr(reuse_order, i32, "reuse_order"),
+        _ptr(reuse_count, i32, "reuse_count"), stride, _ptr(layer_count, i32, "layer_count"),
+        _ptr(embeds, torch.float32, "embeds"), L, _stream(stream))
+    return _ret(st, "vlac_embed_patches", check)
 
 
 def vlac_layer_ratio(ctx, attn_mean, B, L_v, gain_k, reuse_count, out_alpha, out_layer_count,

@@ -61,7 +61,7 @@ void free_all(vlac_ctx* c) {
   void* dev[] = {c->w_head, c->embed, c->g_final, c->rope_cos, c->rope_sin, c->h, c->hdec, c->xa, c->xf,
                  c->qbuf, c->partial, c->rpart, c->counters, c->rows, c->prev_slot, c->n_rows, c->slot_off, c->rank,
                  c->m_layer, c->n_rows_bl, c->statp, c->stat_counters, c->logits, c->tokens,
-                 c->dec_rows, c->terms, c->flags, c->relevance, c->errword, c->scratch_i,
+                 c->dec_rows, c->terms, c->flags, c->embed_list, c->embed_n, c->relevance, c->errword, c->scratch_i,
                  c->zero_tile};
   for (void* p : dev) (void)hipFree(p);
   for (int i = 0; i < c->prof_cap; ++i) {
@@ -175,6 +175,8 @@ int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out) {
   A_(dec_rows, (size_t)ms * mb + ms + (size_t)ms * (mb + 1));
   A_(terms, (size_t)mb * 4096 * 3);
   A_(flags, (size_t)mb * 4096);
+  A_(embed_list, (size_t)mb * 4096);
+  A_(embed_n, mb);
   A_(relevance, (size_t)mb * 4096);
   A_(errword, 1);
   A_(zero_tile, 512);
@@ -356,6 +358,24 @@ int vlac_check(vlac_ctx* ctx, void* stream) {
     VLAC_HIP(hipStreamSynchronize((hipStream_t)stream));
     return VLAC_E_RANGE;
   }
+  return VLAC_OK;
+}
+
+int vlac_embed_patches(vlac_ctx* ctx, const uint8_t* frame_cur, int B, int H, int W, int patch,
+                       const void* w_proj, const int32_t* reuse_order, const int32_t* reuse_count,
+                       int stride, const int32_t* layer_count, float* embeds, int L, void* stream) {
+  if (!ctx || !frame_cur || !w_proj || !embeds) return VLAC_E_NULL;
+  if ((reuse_order == nullptr) != (reuse_count == nullptr)) return VLAC_E_NULL;
+  if (layer_count && !reuse_order) return VLAC_E_NULL;
+  if (B < 1 || B > ctx->cfg.max_batch) return VLAC_E_RANGE;
+  // (8 patches of fp32 pixels are staged in 64 KiB of LDS: 3 patch^2 <= 2048)
+  if (patch < 1 || patch > 26 || H < patch || W < patch || H % patch || W % patch) return VLAC_E_SHAPE;
+  const long long L_v = (long long)(H / patch) * (W / patch);
+  if (L_v > 4096 || L < L_v) return VLAC_E_SHAPE;
+  if (reuse_order && stride < 1) return VLAC_E_RANGE;
+  launch_embed_patches(ctx, frame_cur, B, H, W, patch, (const bf16_t*)w_proj, reuse_order, reuse_count,
+                       stride, layer_count, embeds, L, (hipStream_t)stream);
+  VLAC_HIP(hipGetLastError());
   return VLAC_OK;
 }
 

@@ -128,6 +128,8 @@ struct vlac_ctx {
   int* dec_rows;    // decode row lists
   uint32_t* terms;  // patch terms [max_batch, 4096, 3]
   uint8_t* flags;   // selection flags
+  int* embed_list;  // [max_batch][4096] patches to embed
+  int* embed_n;     // [max_batch]
   float* relevance; // [max_batch, 4096]
   bf16_t* zero_tile; // one operand tile of zeros
   int* errword;     // device error bits
@@ -230,6 +232,11 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, 
                  const NormIn* norm = nullptr);
 // true if launch_gemm may be given a NormIn (RMSNorm fused into the GEMM)
 bool gemm_can_fuse_norm(int n_rows_host, int decode_pos, int kpad);
+
+// embed.hip
+void launch_embed_patches(vlac_ctx* c, const uint8_t* frame, int B, int H, int W, int patch,
+                          const bf16_t* w_proj, const int32_t* reuse_order, const int32_t* reuse_count,
+                          int stride, const int32_t* layer_count, float* embeds, int L, hipStream_t st);
 
 // attn.hip
 // Text tiles per stream that the deferred statistic reduction provides for (text rows
