@@ -34,19 +34,21 @@ KIND_NAMES = {0: "qkv_rope_scatter", 1: "proj_residual", 2: "gate_up_swiglu", 3:
 CLASS_NAMES = {0: "rows<=32 (decode, head)", 1: "rows>32 (prefill)"}
 
 
-def gemm_bytes(cfg, epi, rows):
-    """Algorithmic HBM bytes of one GEMM launch: the bf16 weights once, plus the
-    row operands in and the results out (both small)."""
+def gemm_bytes(cfg, epi, rows, wb=2):
+    """Algorithmic HBM bytes of one GEMM launch: the weights once (wb bytes each: 2 for
+    16-bit operands, 1 for e4m3 codes, then plus 4 bytes of scale per output feature), plus
+    the row operands in and the results out (both small)."""
     d, F = cfg.d_model, cfg.d_ffn
     qkv = cfg.q_dim + 2 * cfg.kv_dim
+    sc = 4 if wb == 1 else 0
     if epi == 0:
-        return 2 * qkv * d + rows * d * 2 + rows * qkv * 2
+        return wb * qkv * d + sc * qkv + rows * d * 2 + rows * qkv * 2
     if epi == 2:
-        return 2 * 2 * F * d + rows * d * 2 + rows * F * 2
+        return wb * 2 * F * d + sc * 2 * F + rows * d * 2 + rows * F * 2
     if epi == 3:
-        return 2 * cfg.vocab * d + rows * d * 2 + rows * cfg.vocab * 4
+        return wb * cfg.vocab * d + sc * cfg.vocab + rows * d * 2 + rows * cfg.vocab * 4
     # epi 1 is used for two shapes (attention output and FFN down): their mean
-    return (2 * d * cfg.q_dim + rows * cfg.q_dim * 2 + 2 * d * F + rows * F * 2) // 2 + rows * d * 8
+    return (wb * d * cfg.q_dim + rows * cfg.q_dim * 2 + wb * d * F + rows * F * 2 + 2 * sc * d) // 2 + rows * d * 8
 
 
 def main():
@@ -63,6 +65,10 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="reused-token sweep on a synthetic frame stream (top-k x tau_task), with the "
                          "paper's operation estimate beside the true count; prints its own JSON line")
+    ap.add_argument("--weights", default="bf16", choices=["bf16", "e4m3"],
+                    help="c2 only. bf16 (default): the benchmark's configuration, weights kept as 16-bit "
+                         "operands; e4m3: weight-only 8-bit storage (beyond the paper), same arithmetic "
+                         "on the quantised weights, half the weight bytes per pass")
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers than the model has")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=32)
@@ -103,7 +109,10 @@ def main():
     seed, H, patch, n_vis, n_txt, top_k, n_redraw = 0, 224, 14, 256, 32, 180, 77
     L = n_vis + n_txt
     n_new = N_ACTION - 1
-    gm = GpuModel(cfg, seed, max_batch=1, max_seq=320, gain_jitter=0.0, gen_device=dev)
+    w8 = args.weights == "e4m3"
+    wb = 1 if w8 else 2
+    gm = GpuModel(cfg, seed, max_batch=1, max_seq=320, gain_jitter=0.0, gen_device=dev,
+                  operand="f16w8" if w8 else "f16")
     ctx, kv = gm.ctx, gm.kv
 
     prev, cur, redrawn = synth.frame_pair(H, H, patch, n_redraw, seed)
@@ -206,7 +215,7 @@ def main():
             rows = 1 if cls == 0 else n_rows
             kernels[kind] = {"name": "gemm_rows<%s> %s" % (KIND_NAMES[epi], CLASS_NAMES[cls]),
                              "launches_per_step": n, "avg_us": tot / n * 1e3, "marker_us": mark / n * 1e3,
-                             "ms_per_step": tot, "bytes": gemm_bytes(cfg, epi, rows)}
+                             "ms_per_step": tot, "bytes": gemm_bytes(cfg, epi, rows, wb)}
     V.vlac_profile_select(ctx, -1)
     # What a bracket adds to the kernel inside it: measured with a kernel that times itself
     # (it spins on the GPU's wall clock for 20 us and stores what it saw), bracketed the same
@@ -227,7 +236,7 @@ def main():
     full_depth_c2 = (nl == 32 and dom < 4)
     roofline = {"bound": "hbm", "kernel": kd["name"], "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": PMC_TRAFFIC_BYTES[dom % 4] if full_depth_c2 else None,
+                "traffic": PMC_TRAFFIC_BYTES[dom % 4] if full_depth_c2 and not w8 else None,
                 "bytes_per_launch": kd["bytes"], "avg_launch_us": round(dur_us, 2),
                 "avg_launch_us_raw_events": round(kd["avg_us"], 2),
                 "event_bracket_overhead_us": round(ev_overhead_us, 2),
@@ -249,9 +258,9 @@ def main():
         torch.cuda.synchronize()
         front[name] = round(float(np.median([a.elapsed_time(b) for a, b in ev[4:]])) * 1e3, 1)
 
-    weight_bytes = 2 * nl * (cfg.d_model * (cfg.q_dim + 2 * cfg.kv_dim) + cfg.q_dim * cfg.d_model +
+    weight_bytes = wb * nl * (cfg.d_model * (cfg.q_dim + 2 * cfg.kv_dim) + cfg.q_dim * cfg.d_model +
                              3 * cfg.d_model * cfg.d_ffn)
-    head_bytes = 2 * cfg.vocab * cfg.d_model
+    head_bytes = wb * cfg.vocab * cfg.d_model
     out = {
         "metric": "recomputed_token_prefill_tok_per_s",
         "value": round(n_rows / (ms_prefill * 1e-3), 1),
@@ -261,7 +270,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": "c2: OpenVLA-7B shape, 1 stream, 256 visual + 32 text tokens, "
-                               "77/256 patches re-drawn, top-k 180, 7 action tokens",
+                               "77/256 patches re-drawn, top-k 180, 7 action tokens"
+                               + (", weights stored as e4m3 codes (weight-only 8-bit, beyond the paper)" if w8 else ""),
                    "n_layers": nl, "rows_recomputed": n_rows, "tokens_reused": n_reused},
         "step_latency_ms": round(ms_step, 4),
         "phase_ms": {"select+ratio": round(float(ms_sel), 4), "sparse_prefill": round(float(ms_prefill), 4),

@@ -17,7 +17,7 @@ class GpuModel:
         self.max_batch, self.max_seq = max_batch, max_seq
         self.ccfg = V.ModelCfg(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads,
                                cfg.head_dim, cfg.d_ffn, cfg.vocab, cfg.rms_eps, cfg.rope_base,
-                               max_batch, max_seq, {"bf16": 0, "f16": 1}[operand])
+                               max_batch, max_seq, {"bf16": 0, "f16": 1, "f16w8": 2}[operand])
         self.ctx = V.vlac_create(self.ccfg)
         for l in range(cfg.n_layers):
             w = {k: v.to(device) for k, v in

@@ -54,7 +54,7 @@ typedef struct {
   float rms_eps, rope_base;
   int32_t max_batch; /* streams (independent environments, each with its own KV cache) */
   int32_t max_seq;   /* cache slots per stream: L + decoded action tokens, rounded up to 32 */
-  int32_t operand_dtype; /* VLAC_OPERAND_BF16 or VLAC_OPERAND_F16, see below */
+  int32_t operand_dtype; /* VLAC_OPERAND_BF16, VLAC_OPERAND_F16 or VLAC_OPERAND_F16_W8, see below */
 } vlac_model_cfg;
 
 /* 16-bit type of the matrix-core operands (weights as stored inside the context,
@@ -63,7 +63,15 @@ typedef struct {
  * bf16.  F16 re-encodes them as fp16, which is exact for every bf16 value of
  * magnitude in [2^-14, 65504], and rounds activations 8 times finer than bf16;
  * conversions to fp16 saturate at +-65504. */
-enum { VLAC_OPERAND_BF16 = 0, VLAC_OPERAND_F16 = 1 };
+enum { VLAC_OPERAND_BF16 = 0, VLAC_OPERAND_F16 = 1, VLAC_OPERAND_F16_W8 = 2 };
+/* F16_W8 (beyond the paper: weight-only 8-bit storage, aimed at the decode passes that the
+ * method leaves untouched and that are bound by streaming the weights): as F16, but the
+ * context keeps every weight matrix as OCP e4m3 codes with one power-of-two scale per
+ * output feature (the smallest with max|w_row| / scale <= 448; codes by round to nearest,
+ * ties to even; see vlac_quantize_e4m3), and the kernels expand the codes to fp16 in
+ * registers, which is exact.  The weights handed over are bf16 as always; the result is
+ * that of the F16 mode with the quantised weights.  Serves up to 1023 rows per launch
+ * (one stream, small batches): larger prefills return VLAC_E_STATE. */
 
 /* One decoder layer, device pointers, bf16, row-major [out_features, in_features]
  * (y = x W^T).  wqkv rows: all query heads, then all key heads, then all value
@@ -133,6 +141,12 @@ int vlac_profile_read2(vlac_ctx* ctx, double* total_ms, double* marker_ms, int* 
  * (bracket - the kernel's own time) over the last 32.  Uses the split-K workspace: call it
  * while nothing else of this context runs. */
 int vlac_profile_bracket_cost(vlac_ctx* ctx, void* stream, double* cost_us);
+
+/* The quantiser of VLAC_OPERAND_F16_W8 on its own: w device bf16 [N, K] row-major ->
+ * out_codes device uint8 [N, K] (OCP e4m3: 1 sign, 4 exponent bits of bias 7, 3 mantissa
+ * bits, subnormals, no infinities) and out_scales device fp32 [N], with
+ * w[n, k] ~ value(out_codes[n, k]) * out_scales[n].  Needs no context. */
+int vlac_quantize_e4m3(const void* w, int N, int K, uint8_t* out_codes, float* out_scales, void* stream);
 
 /* Alg. 1 (Sec. 3.2 Eq. sim, Eq. topk; Sec. 3.3 Eq. ptask, Eq. pfinal).
  *

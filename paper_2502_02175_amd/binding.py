@@ -27,7 +27,7 @@ class ModelCfg(C.Structure):
         ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("operand_dtype", C.c_int32)]
 
 
-OPERAND_BF16, OPERAND_F16 = 0, 1
+OPERAND_BF16, OPERAND_F16, OPERAND_F16_W8 = 0, 1, 2
 
 
 class LayerW(C.Structure):
@@ -65,6 +65,7 @@ def lib():
         L.vlac_profile_bracket_cost.argtypes = [vp, vp, C.POINTER(C.c_double)]
         L.vlac_select_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, f32,
                                          vp, vp, vp, vp, i32, vp]
+        L.vlac_quantize_e4m3.argtypes = [vp, i32, i32, vp, vp, vp]
         L.vlac_embed_patches.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, i32, vp]
         L.vlac_layer_ratio.argtypes = [vp, vp, i32, i32, f32, vp, vp, vp, vp]
         L.vlac_sparse_prefill.argtypes = [vp, vp, i32, i32, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
@@ -73,7 +74,7 @@ def lib():
                      "vlac_set_head_weights", "vlac_reset_stream", "vlac_check",
                      "vlac_profile_select", "vlac_profile_read", "vlac_profile_read2",
                      "vlac_profile_bracket_cost",
-                     "vlac_select_static", "vlac_embed_patches", "vlac_layer_ratio", "vlac_sparse_prefill",
+                     "vlac_select_static", "vlac_embed_patches", "vlac_quantize_e4m3", "vlac_layer_ratio", "vlac_sparse_prefill",
                      "vlac_decode_action"):
             getattr(L, name).restype = i32
         _LIB = L
@@ -209,6 +210,15 @@ def vlac_select_static(ctx, frame_prev, frame_cur, B, H, W, patch, tau_num, tau_
         _ptr(out_count, torch.int32, "out_count"), _ptr(out_relevance, torch.float32, "out_relevance"),
         stride, _stream(stream))
     return _ret(st, "vlac_select_static", check)
+
+
+def vlac_quantize_e4m3(w, out_codes, out_scales, stream=None, check=True):
+    """w: bf16 GPU tensor [N, K]; out_codes uint8 [N, K]; out_scales fp32 [N]."""
+    import torch
+    N, K = w.shape
+    st = lib().vlac_quantize_e4m3(_ptr(w, torch.bfloat16, "w"), N, K, _ptr(out_codes, torch.uint8, "out_codes"),
+                                  _ptr(out_scales, torch.float32, "out_scales"), _stream(stream))
+    return _ret(st, "vlac_quantize_e4m3", check)
 
 
 def vlac_embed_patches(ctx, frame_cur, B, H, W, patch, w_proj, reuse_order, reuse_count, stride,

@@ -43,7 +43,8 @@ int check_cfg(const vlac_model_cfg* m) {
   if (m->n_q_heads % 4 || m->n_q_heads % m->n_kv_heads) return VLAC_E_SHAPE;
   if (m->max_seq > 65536 || m->max_batch > 32767) return VLAC_E_RANGE;
   if (!(m->rms_eps > 0.f) || !(m->rope_base > 1.f)) return VLAC_E_RANGE;
-  if (m->operand_dtype != VLAC_OPERAND_BF16 && m->operand_dtype != VLAC_OPERAND_F16)
+  if (m->operand_dtype != VLAC_OPERAND_BF16 && m->operand_dtype != VLAC_OPERAND_F16 &&
+      m->operand_dtype != VLAC_OPERAND_F16_W8)
     return VLAC_E_RANGE;
   return VLAC_OK;
 }
@@ -53,12 +54,13 @@ void free_all(vlac_ctx* c) {
   if (c->layers) {
     for (int l = 0; l < c->cfg.n_layers; ++l) {
       void* lw[] = {c->layers[l].wqkv, c->layers[l].wo, c->layers[l].wgu,
-                    c->layers[l].wdown, c->layers[l].g_attn, c->layers[l].g_ffn};
+                    c->layers[l].wdown, c->layers[l].g_attn, c->layers[l].g_ffn,
+                    c->layers[l].s_qkv, c->layers[l].s_o, c->layers[l].s_gu, c->layers[l].s_down};
       for (void* p : lw) (void)hipFree(p);
     }
     free(c->layers);
   }
-  void* dev[] = {c->w_head, c->embed, c->g_final, c->rope_cos, c->rope_sin, c->h, c->hdec, c->xa, c->xf,
+  void* dev[] = {c->w_head, c->s_head, c->scale_tmp, c->embed, c->g_final, c->rope_cos, c->rope_sin, c->h, c->hdec, c->xa, c->xf,
                  c->qbuf, c->partial, c->rpart, c->counters, c->rows, c->prev_slot, c->n_rows, c->slot_off, c->rank,
                  c->m_layer, c->n_rows_bl, c->statp, c->stat_counters, c->logits, c->tokens,
                  c->dec_rows, c->terms, c->flags, c->embed_list, c->embed_n, c->relevance, c->errword, c->scratch_i,
@@ -115,7 +117,8 @@ int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out) {
   ctx->kpad_f = round_up(m.d_ffn, 64);
   ctx->max_rows = m.max_batch * m.max_seq;
   ctx->prof_kind = -1;
-  ctx->f16 = (m.operand_dtype == VLAC_OPERAND_F16);
+  ctx->f16 = (m.operand_dtype == VLAC_OPERAND_F16 || m.operand_dtype == VLAC_OPERAND_F16_W8);
+  ctx->w8 = (m.operand_dtype == VLAC_OPERAND_F16_W8);
   ctx->layers = (LayerW*)calloc(m.n_layers, sizeof(LayerW));
   ctx->layer_set = (uint8_t*)calloc(m.n_layers, 1);
   ctx->filled = (uint8_t*)calloc(m.max_batch, 1);
@@ -133,15 +136,27 @@ int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out) {
   ctx->n_counters = 1 << 16;
   ctx->stat_tt = ms / 32 + 1;
 #define A_(ptr, n) if (e == hipSuccess) e = dalloc(&ctx->ptr, (size_t)(n))
+  const int wdiv = ctx->w8 ? 2 : 1;  // e4m3 codes take half the bytes of 16-bit operands
+  int max_out = ctx->qkv_dim > 2 * m.d_ffn ? ctx->qkv_dim : 2 * m.d_ffn;
+  if (m.vocab > max_out) max_out = m.vocab;
+  if (m.d_model > max_out) max_out = m.d_model;
   for (int l = 0; l < nl && e == hipSuccess; ++l) {
-    A_(layers[l].wqkv, frag_elems(ctx->qkv_dim, ctx->kpad_d));
-    A_(layers[l].wo, frag_elems(m.d_model, ctx->kpad_q));
-    A_(layers[l].wgu, frag_elems(2 * m.d_ffn, ctx->kpad_d));
-    A_(layers[l].wdown, frag_elems(m.d_model, ctx->kpad_f));
+    A_(layers[l].wqkv, frag_elems(ctx->qkv_dim, ctx->kpad_d) / wdiv);
+    A_(layers[l].wo, frag_elems(m.d_model, ctx->kpad_q) / wdiv);
+    A_(layers[l].wgu, frag_elems(2 * m.d_ffn, ctx->kpad_d) / wdiv);
+    A_(layers[l].wdown, frag_elems(m.d_model, ctx->kpad_f) / wdiv);
+    if (ctx->w8) {
+      A_(layers[l].s_qkv, ctx->qkv_dim);
+      A_(layers[l].s_o, m.d_model);
+      A_(layers[l].s_gu, 2 * m.d_ffn);
+      A_(layers[l].s_down, m.d_model);
+    }
     A_(layers[l].g_attn, m.d_model);
     A_(layers[l].g_ffn, m.d_model);
   }
-  A_(w_head, frag_elems(m.vocab, ctx->kpad_d));
+  A_(w_head, frag_elems(m.vocab, ctx->kpad_d) / wdiv);
+  if (ctx->w8) A_(s_head, m.vocab);
+  if (ctx->w8) A_(scale_tmp, max_out);
   A_(embed, (size_t)m.vocab * m.d_model);
   A_(g_final, m.d_model);
   A_(rope_cos, (size_t)ms * (m.head_dim / 2));
@@ -228,6 +243,25 @@ int vlac_destroy(vlac_ctx* ctx) {
   return VLAC_OK;
 }
 
+// Weights [N, K] row-major -> the context's storage (N is a multiple of 32 for every matrix)
+static void pack_matrix(vlac_ctx* ctx, const bf16_t* src, int N, int K, bf16_t* dst, float* scales_packed,
+                        int kpad, int mode, int p0, int p1, int p2, hipStream_t st) {
+  if (ctx->w8) {
+    launch_row_scales(src, N, K, ctx->scale_tmp, st);
+    launch_pack_e4m3(src, N, K, ctx->scale_tmp, dst, scales_packed, N, kpad, mode, p0, p1, p2, st);
+  } else {
+    launch_pack(ctx->f16, src, N, K, dst, N, kpad, mode, p0, p1, p2, st);
+  }
+}
+
+int vlac_quantize_e4m3(const void* w, int N, int K, uint8_t* out_codes, float* out_scales, void* stream) {
+  if (!w || !out_codes || !out_scales) return VLAC_E_NULL;
+  if (N < 1 || K < 1) return VLAC_E_RANGE;
+  launch_row_scales((const bf16_t*)w, N, K, out_scales, (hipStream_t)stream);
+  launch_quantize_e4m3((const bf16_t*)w, N, K, out_scales, out_codes, (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? VLAC_OK : VLAC_E_HIP;
+}
+
 int vlac_set_layer_weights(vlac_ctx* ctx, int layer, const vlac_layer_w* w, void* stream) {
   if (!ctx || !w) return VLAC_E_NULL;
   if (layer < 0 || layer >= ctx->cfg.n_layers) return VLAC_E_RANGE;
@@ -236,12 +270,12 @@ int vlac_set_layer_weights(vlac_ctx* ctx, int layer, const vlac_layer_w* w, void
   const vlac_model_cfg& m = ctx->cfg;
   hipStream_t st = (hipStream_t)stream;
   LayerW& L = ctx->layers[layer];
-  launch_pack(ctx->f16, (const bf16_t*)w->wqkv, ctx->qkv_dim, m.d_model, L.wqkv, ctx->qkv_dim, ctx->kpad_d, 1,
-              ctx->q_dim, ctx->kv_dim, m.head_dim, st);
-  launch_pack(ctx->f16, (const bf16_t*)w->wo, m.d_model, ctx->q_dim, L.wo, m.d_model, ctx->kpad_q, 0, 0, 0, 0, st);
-  launch_pack(ctx->f16, (const bf16_t*)w->w_gate_up, 2 * m.d_ffn, m.d_model, L.wgu, 2 * m.d_ffn, ctx->kpad_d, 2,
-              m.d_ffn, 0, 0, st);
-  launch_pack(ctx->f16, (const bf16_t*)w->w_down, m.d_model, m.d_ffn, L.wdown, m.d_model, ctx->kpad_f, 0, 0, 0, 0, st);
+  pack_matrix(ctx, (const bf16_t*)w->wqkv, ctx->qkv_dim, m.d_model, L.wqkv, L.s_qkv, ctx->kpad_d, 1, ctx->q_dim,
+              ctx->kv_dim, m.head_dim, st);
+  pack_matrix(ctx, (const bf16_t*)w->wo, m.d_model, ctx->q_dim, L.wo, L.s_o, ctx->kpad_q, 0, 0, 0, 0, st);
+  pack_matrix(ctx, (const bf16_t*)w->w_gate_up, 2 * m.d_ffn, m.d_model, L.wgu, L.s_gu, ctx->kpad_d, 2, m.d_ffn, 0,
+              0, st);
+  pack_matrix(ctx, (const bf16_t*)w->w_down, m.d_model, m.d_ffn, L.wdown, L.s_down, ctx->kpad_f, 0, 0, 0, 0, st);
   launch_bf16_to_f32((const bf16_t*)w->g_attn, L.g_attn, m.d_model, st);
   launch_bf16_to_f32((const bf16_t*)w->g_ffn, L.g_ffn, m.d_model, st);
   VLAC_HIP(hipGetLastError());
@@ -254,7 +288,7 @@ int vlac_set_head_weights(vlac_ctx* ctx, const void* g_final, const void* w_head
   if (!ctx || !g_final || !w_head || !embed) return VLAC_E_NULL;
   const vlac_model_cfg& m = ctx->cfg;
   hipStream_t st = (hipStream_t)stream;
-  launch_pack(ctx->f16, (const bf16_t*)w_head, m.vocab, m.d_model, ctx->w_head, m.vocab, ctx->kpad_d, 0, 0, 0, 0, st);
+  pack_matrix(ctx, (const bf16_t*)w_head, m.vocab, m.d_model, ctx->w_head, ctx->s_head, ctx->kpad_d, 0, 0, 0, 0, st);
   launch_bf16_to_f32((const bf16_t*)g_final, ctx->g_final, m.d_model, st);
   VLAC_HIP(hipMemcpyAsync(ctx->embed, embed, (size_t)m.vocab * m.d_model * sizeof(bf16_t),
                           hipMemcpyDeviceToDevice, st));
@@ -462,12 +496,12 @@ void run_layer(vlac_ctx* c, int layer, int B, int rows_cap, int rows_cap_per_str
   else
     launch_rmsnorm_rows(c->f16, resid_in, resid_stride, rows, n_rows, n_host, decode_pos, rows_cap,
                         W.g_attn, m.rms_eps, m.d_model, c->xa, kc_d, st);
-  launch_gemm(c, EPI_QKV, W.wqkv, c->qkv_dim / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st);
+  launch_gemm(c, EPI_QKV, W.wqkv, W.s_qkv, c->qkv_dim / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st);
   *pending = 0;
   launch_attention(c, layer, B, rows_cap_per_stream, L_v, L_t, rows, slot_off, decode_pos, kv,
                    out_attn_mean, st);
   e.resid_src = resid_in; e.resid_seq_stride = resid_stride;
-  const int s_o = launch_gemm(c, EPI_RESID, W.wo, m.d_model / 32, c->kpad_q, c->xa, n_rows, n_host,
+  const int s_o = launch_gemm(c, EPI_RESID, W.wo, W.s_o, m.d_model / 32, c->kpad_q, c->xa, n_rows, n_host,
                               rows_cap, e, st);
   if (rows_cap > 32 && s_o > 1)  // the few-rows kernel adds its splits up itself
     launch_resid_norm_rows(c->f16, resid_in, resid_stride, c->rpart, s_o, rows_cap, c->h, m.max_seq,
@@ -476,9 +510,9 @@ void run_layer(vlac_ctx* c, int layer, int B, int rows_cap, int rows_cap_per_str
   else
     launch_rmsnorm_rows(c->f16, c->h, m.max_seq, rows, n_rows, n_host, decode_pos, rows_cap, W.g_ffn,
                         m.rms_eps, m.d_model, c->xa, kc_d, st);
-  launch_gemm(c, EPI_SWIGLU, W.wgu, 2 * m.d_ffn / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st);
+  launch_gemm(c, EPI_SWIGLU, W.wgu, W.s_gu, 2 * m.d_ffn / 32, c->kpad_d, c->xa, n_rows, n_host, rows_cap, e, st);
   e.resid_src = c->h; e.resid_seq_stride = m.max_seq;
-  const int s_d = launch_gemm(c, EPI_RESID, W.wdown, m.d_model / 32, c->kpad_f, c->xf, n_rows, n_host,
+  const int s_d = launch_gemm(c, EPI_RESID, W.wdown, W.s_down, m.d_model / 32, c->kpad_f, c->xf, n_rows, n_host,
                               rows_cap, e, st);
   *pending = (rows_cap > 32 && s_d > 1) ? s_d : 0;
 }
@@ -535,17 +569,17 @@ void run_layer_decode(vlac_ctx* c, int layer, int B, int pos, bf16_t* kv, Decode
   e.xf = c->xf; e.kc_f = c->kpad_f / 16; e.d_ffn = m.d_ffn;
 
   NormIn n = decode_norm(c, B, r, W.g_attn, true);
-  launch_gemm(c, EPI_QKV, W.wqkv, c->qkv_dim / 32, c->kpad_d, c->xa, nullptr, B, B, e, st, &n);
+  launch_gemm(c, EPI_QKV, W.wqkv, W.s_qkv, c->qkv_dim / 32, c->kpad_d, c->xa, nullptr, B, B, e, st, &n);
   launch_attention(c, layer, B, 1, 0, 0, nullptr, nullptr, pos, kv, nullptr, st);
   float* hrow = c->hdec + (size_t)r.cur * m.max_batch * m.d_model;
   e.resid_src = hrow; e.h = hrow;
-  const int s_o = launch_gemm(c, EPI_RESID, W.wo, m.d_model / 32, c->kpad_q, c->xa, nullptr, B, B, e, st);
+  const int s_o = launch_gemm(c, EPI_RESID, W.wo, W.s_o, m.d_model / 32, c->kpad_q, c->xa, nullptr, B, B, e, st);
   r.pending = s_o > 1 ? s_o : 0;
   n = decode_norm(c, B, r, W.g_ffn, true);
-  launch_gemm(c, EPI_SWIGLU, W.wgu, 2 * m.d_ffn / 32, c->kpad_d, c->xa, nullptr, B, B, e, st, &n);
+  launch_gemm(c, EPI_SWIGLU, W.wgu, W.s_gu, 2 * m.d_ffn / 32, c->kpad_d, c->xa, nullptr, B, B, e, st, &n);
   hrow = c->hdec + (size_t)r.cur * m.max_batch * m.d_model;
   e.resid_src = hrow; e.h = hrow;
-  const int s_d = launch_gemm(c, EPI_RESID, W.wdown, m.d_model / 32, c->kpad_f, c->xf, nullptr, B, B, e, st);
+  const int s_d = launch_gemm(c, EPI_RESID, W.wdown, W.s_down, m.d_model / 32, c->kpad_f, c->xf, nullptr, B, B, e, st);
   r.pending = s_d > 1 ? s_d : 0;
 }
 
@@ -559,17 +593,17 @@ void run_head(vlac_ctx* c, int B, int pos, float* logits, size_t logits_stride, 
   e.decode_pos = pos;
   e.logits = logits; e.vocab = m.vocab; e.logits_stride = logits_stride;
   if (fused) {
-    launch_gemm(c, EPI_LOGITS, c->w_head, m.vocab / 32, c->kpad_d, c->xa, nullptr, B, B, e, st, fused);
+    launch_gemm(c, EPI_LOGITS, c->w_head, c->s_head, m.vocab / 32, c->kpad_d, c->xa, nullptr, B, B, e, st, fused);
   } else if (gemm_can_fuse_norm(B, pos, c->kpad_d)) {
     NormIn n;
     memset(&n, 0, sizeof(n));
     n.src = c->h + (size_t)pos * m.d_model; n.src_stride = (size_t)m.max_seq * m.d_model;
     n.gain = c->g_final; n.eps = m.rms_eps; n.d = m.d_model;
-    launch_gemm(c, EPI_LOGITS, c->w_head, m.vocab / 32, c->kpad_d, c->xa, nullptr, B, B, e, st, &n);
+    launch_gemm(c, EPI_LOGITS, c->w_head, c->s_head, m.vocab / 32, c->kpad_d, c->xa, nullptr, B, B, e, st, &n);
   } else {
     launch_rmsnorm_rows(c->f16, c->h, m.max_seq, nullptr, nullptr, B, pos, B, c->g_final, m.rms_eps,
                         m.d_model, c->xa, c->kpad_d / 16, st);
-    launch_gemm(c, EPI_LOGITS, c->w_head, m.vocab / 32, c->kpad_d, c->xa, nullptr, B, B, e, st);
+    launch_gemm(c, EPI_LOGITS, c->w_head, c->s_head, m.vocab / 32, c->kpad_d, c->xa, nullptr, B, B, e, st);
   }
   launch_argmax(logits, logits_stride, B, m.vocab, out_token, out_stride, token_copy, st);
 }
@@ -607,6 +641,7 @@ int vlac_sparse_prefill(vlac_ctx* ctx, const float* embeds, int B, int L_v, int 
   const int nl = m.n_layers;
   launch_plan(ctx, B, L_v, L_t, reuse_order, reuse_count, stride, layer_count, st);
   const int rows_cap = B * L;
+  if (ctx->w8 && rows_cap >= 1024) return VLAC_E_STATE;  // e4m3 weights: no many-rows kernel
   const int n_host = reuse_order ? -1 : rows_cap;
   int pending = 0;
   for (int l = 0; l < nl; ++l) {

@@ -80,13 +80,15 @@ __device__ inline f32x16 mfma32(const uint4& a, const uint4& b, const f32x16& c)
 enum { VLAC_ERR_BAD_INDEX = 1 };  // bits of the device-side error word
 
 struct LayerW {
-  bf16_t *wqkv, *wo, *wgu, *wdown;  // fragment order
+  bf16_t *wqkv, *wo, *wgu, *wdown;  // fragment order (16-bit operands, or e4m3 codes)
   float *g_attn, *g_ffn;
+  float *s_qkv, *s_o, *s_gu, *s_down;  // e4m3 weights: scale per packed output row
 };
 
 struct vlac_ctx {
   vlac_model_cfg cfg;
   bool f16;  // operands are fp16 (else bf16)
+  bool w8;   // weights are stored as e4m3 codes + a scale per output feature (f16 operands)
   int device;
   int last_hip;
   // derived
@@ -98,6 +100,8 @@ struct vlac_ctx {
   uint8_t* layer_set;
   bool head_set;
   bf16_t *w_head, *embed;
+  float* s_head;
+  float* scale_tmp;  // scales in source row order while a matrix is being packed
   float* g_final;
   float *rope_cos, *rope_sin;  // [max_seq, hd/2]
   // workspace (device)
@@ -183,6 +187,12 @@ void launch_argmax(const float* logits, size_t logits_stride, int B, int vocab, 
                    int out_stride, int32_t* out2, hipStream_t st);
 void launch_embed_rows(const bf16_t* embed, const int32_t* tokens, int B, int d, int vocab, float* h,
                        int max_seq, int pos, hipStream_t st);
+// e4m3 storage: scales of the N source rows, then codes in fragment order (two k-tiles per
+// 16-byte lane slot) and the scales in packed row order
+void launch_row_scales(const bf16_t* src, int N, int K, float* scales, hipStream_t st);
+void launch_pack_e4m3(const bf16_t* src, int N, int K, const float* scales, bf16_t* dst, float* scales_packed,
+                      int n_pack, int kpad, int mode, int p0, int p1, int p2, hipStream_t st);
+void launch_quantize_e4m3(const bf16_t* src, int N, int K, const float* scales, uint8_t* codes, hipStream_t st);
 void launch_pack(bool to_f16, const bf16_t* src, int N, int K, bf16_t* dst, int n_pack, int kpad,
                  int mode, int p0, int p1, int p2, hipStream_t st);
 void launch_bf16_to_f32(const bf16_t* src, float* dst, int n, hipStream_t st);
@@ -227,7 +237,8 @@ int gemm_init();  // one-time kernel attribute setup; returns hipError_t
 // NOT in the residual stream yet but in e.rpart as S partial rows (more than 32 rows:
 // always; at most 32 rows: if e.defer_split is set) for the consumer to add up
 // (launch_resid_norm_rows, or NormIn::part of the next projection)
-int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, const bf16_t* xp,
+int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, const float* wscale, int n_blocks, int kpad,
+                const bf16_t* xp,
                  const int* n_rows, int n_rows_host, int rows_cap, const GemmEpi& e, hipStream_t st,
                  const NormIn* norm = nullptr);
 // true if launch_gemm may be given a NormIn (RMSNorm fused into the GEMM)

@@ -34,7 +34,7 @@
 // Main loop, split-K hand-over and epilogue for a row block with exactly NA active
 // 32-row tiles (a template parameter, so that every loop is unrolled without guards
 // and the compiler can count the loads in flight exactly).
-template <int NA, int MT, int EPI, bool F16>
+template <int NA, int MT, int EPI, bool F16, bool W8>
 __device__ __forceinline__ void rows_body(const GemmArgs& a, uint4* lds, int* s_last, int tile,
                                           int s, int mb, int n_rows, uint32_t pf0, uint32_t pf1) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -44,7 +44,8 @@ __device__ __forceinline__ void rows_body(const GemmArgs& a, uint4* lds, int* s_
   const int KC = 4 * a.KS;
   const int q = a.KS / a.S, r = a.KS % a.S;
   const int ks0 = s * q + min(s, r), n_ks = q + (s < r ? 1 : 0);
-  const uint4* wsrc = a.wp + ((size_t)(wave_on ? nb : a.NB - 1) * KC + 4 * ks0) * 64 + lane;
+  // (e4m3 weights: a 16-byte lane slot holds two k-tiles, a step is two slots per wave)
+  const uint4* wsrc = a.wp + ((size_t)(wave_on ? nb : a.NB - 1) * (W8 ? KC / 2 : KC) + (W8 ? 2 : 4) * ks0) * 64 + lane;
   const uint4* xsrc = a.xp + ((size_t)(row0 >> 5) * KC + 4 * ks0) * 64 + tid;
 
   f32x16 acc[NA];
@@ -65,11 +66,13 @@ __device__ __forceinline__ void rows_body(const GemmArgs& a, uint4* lds, int* s_
   // step i of this workgroup covers k-tiles 4i .. 4i+3 of its K range
 #define VLAC_LOAD_B(i, P)                                   \
   {                                                         \
-    const size_t k_ = (size_t)min((i), n_ks - 1) * 256;     \
+    const size_t k_ = (size_t)min((i), n_ks - 1) * (W8 ? 128 : 256); \
     P##_0 = wsrc[k_];                                       \
     P##_1 = wsrc[k_ + 64];                                  \
-    P##_2 = wsrc[k_ + 128];                                 \
-    P##_3 = wsrc[k_ + 192];                                 \
+    if constexpr (!W8) {                                    \
+      P##_2 = wsrc[k_ + 128];                               \
+      P##_3 = wsrc[k_ + 192];                               \
+    }                                                       \
   }
 #define VLAC_LOAD_A(i, P)                                             \
   {                                                                   \
@@ -89,6 +92,15 @@ __device__ __forceinline__ void rows_body(const GemmArgs& a, uint4* lds, int* s_
 #define VLAC_MMA(c, BW)                                                       \
   _Pragma("unroll") for (int mt = 0; mt < NA; ++mt) acc[mt] =                 \
       mfma32<F16>(BW, lds[(buf_ * MT + mt) * 256 + (c) * 64 + lane], acc[mt]);
+  // the weight tile of k-tile c of a step: a register of its own, or half of a slot of codes
+#define VLAC_MMA4(P)                                                                          \
+  if constexpr (W8) {                                                                         \
+    const uint4 w0_ = e4m3_slot_half(B##P##_0, 0), w1_ = e4m3_slot_half(B##P##_0, 1);         \
+    const uint4 w2_ = e4m3_slot_half(B##P##_1, 0), w3_ = e4m3_slot_half(B##P##_1, 1);         \
+    VLAC_MMA(0, w0_) VLAC_MMA(1, w1_) VLAC_MMA(2, w2_) VLAC_MMA(3, w3_)                       \
+  } else {                                                                                    \
+    VLAC_MMA(0, B##P##_0) VLAC_MMA(1, B##P##_1) VLAC_MMA(2, B##P##_2) VLAC_MMA(3, B##P##_3)   \
+  }
   // Step i: stage slot P held step i (its activation tiles went to LDS during step i-1,
   // its weight tiles are consumed now) and is refilled with step i+4; the activation
   // tiles of step i+1 (slot PN) go to the other LDS buffer.  The phases are fenced
@@ -99,7 +111,7 @@ __device__ __forceinline__ void rows_body(const GemmArgs& a, uint4* lds, int* s_
     __syncthreads();                                                          \
     VLAC_LOAD_A((i) + 4, A##P)                                                \
     __builtin_amdgcn_sched_barrier(0);                                        \
-    VLAC_MMA(0, B##P##_0) VLAC_MMA(1, B##P##_1) VLAC_MMA(2, B##P##_2) VLAC_MMA(3, B##P##_3) \
+    VLAC_MMA4(P)                                                              \
     __builtin_amdgcn_sched_barrier(0);                                        \
     VLAC_LOAD_B((i) + 4, B##P)                                                \
     __builtin_amdgcn_sched_barrier(0);                                        \
@@ -130,12 +142,19 @@ __device__ __forceinline__ void rows_body(const GemmArgs& a, uint4* lds, int* s_
       if (i0 + 2 < n_ks) VLAC_STEP(i0 + 2, 2, 3)
     }
   }
+#undef VLAC_MMA4
 #undef VLAC_MMA
 #undef VLAC_STEP
 #undef VLAC_STORE_A
 #undef VLAC_LOAD_A
 #undef VLAC_LOAD_B
 
+  if constexpr (W8) {
+    if (wave_on) {
+#pragma unroll
+      for (int mt = 0; mt < NA; ++mt) scale_tile(a.wscale, nb, lane >> 5, acc[mt]);
+    }
+  }
   if (EPI == EPI_RESID && a.S > 1) {
     // Projection + residual with split K: every split writes its partial rows
     // [split][row][feature] and is done; the row kernel that follows (residual add +
@@ -204,7 +223,7 @@ __device__ __forceinline__ void rows_body(const GemmArgs& a, uint4* lds, int* s_
   }
 }
 
-template <int MT, int EPI, bool F16>
+template <int MT, int EPI, bool F16, bool W8>
 __global__ __launch_bounds__(256) void gemm_rows_kernel(GemmArgs a) {
   extern __shared__ uint4 lds[];  // [2][MT][256]: two stages of MT activation tiles x 4 k-tiles
   __shared__ int s_last;
@@ -238,9 +257,9 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(GemmArgs a) {
     const int q = a.KS / a.S, r = a.KS % a.S;
     const int ks0 = s * q + min(s, r), n_ks = q + (s < r ? 1 : 0);
     if (n_ks >= 4) {
-      const uint32_t* pw = (const uint32_t*)(a.wp + ((size_t)nb * 4 * a.KS + 4 * ks0) * 64) + lane * 32;
+      const uint32_t* pw = (const uint32_t*)(a.wp + ((size_t)nb * 4 * a.KS + 4 * ks0) * (W8 ? 32 : 64)) + lane * 32;
       pf0 = pw[0];
-      pf1 = pw[2048];
+      pf1 = pw[W8 ? 0 : 2048];
     }
   }
   const int n_rows = a.n_rows_val >= 0 ? a.n_rows_val : *a.n_rows;
@@ -248,10 +267,10 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(GemmArgs a) {
   if (row0 >= n_rows) return;
   static_assert(MT == 4, "row blocks are 4 tiles of 32 rows");
   switch (min(MT, (n_rows - row0 + 31) >> 5)) {
-    case 1: rows_body<1, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows, pf0, pf1); break;
-    case 2: rows_body<2, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows, pf0, pf1); break;
-    case 3: rows_body<3, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows, pf0, pf1); break;
-    default: rows_body<4, MT, EPI, F16>(a, lds, &s_last, tile, s, mb, n_rows, pf0, pf1); break;
+    case 1: rows_body<1, MT, EPI, F16, W8>(a, lds, &s_last, tile, s, mb, n_rows, pf0, pf1); break;
+    case 2: rows_body<2, MT, EPI, F16, W8>(a, lds, &s_last, tile, s, mb, n_rows, pf0, pf1); break;
+    case 3: rows_body<3, MT, EPI, F16, W8>(a, lds, &s_last, tile, s, mb, n_rows, pf0, pf1); break;
+    default: rows_body<4, MT, EPI, F16, W8>(a, lds, &s_last, tile, s, mb, n_rows, pf0, pf1); break;
   }
 }
 
@@ -275,7 +294,7 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(GemmArgs a) {
 //   X_NORM4/8 RMSNorm of fp32 rows of at most 4096 / 8192 elements, slices [k/8][row] in LDS
 enum { X_GLOBAL = 0, X_NORM4 = 1, X_NORM8 = 2 };
 
-template <int EPI, bool F16, int XMODE>
+template <int EPI, bool F16, int XMODE, bool W8>
 __global__ __launch_bounds__(256, XMODE == X_NORM8 ? 2 : 3) void gemm_few_kernel(GemmArgs a) {
   __shared__ float red[3][16][64];
   extern __shared__ uint4 xlds[];  // operand slices [k/8 - lo8][row]
@@ -285,9 +304,12 @@ __global__ __launch_bounds__(256, XMODE == X_NORM8 ? 2 : 3) void gemm_few_kernel
   const int n_rows = min(a.n_rows_val >= 0 ? a.n_rows_val : *a.n_rows, 32);
   if (n_rows <= 0) return;
   const int KC = 4 * a.KS;
-  const int per = (KC + a.S - 1) / a.S, c_lo = s * per, c_hi = min(KC, c_lo + per);
-  const int perw = (max(c_hi - c_lo, 0) + 3) / 4, w_lo = c_lo + w * perw, w_hi = min(c_hi, w_lo + perw);
-  const uint4* wsrc = a.wp + (size_t)nb * KC * 64 + lane;
+  // (e4m3 weights come two k-tiles to a 16-byte slot: ranges start and end on even tiles)
+  const int ev = W8 ? 1 : 0;
+  const int per = ((KC + a.S - 1) / a.S + ev) & ~ev, c_lo = s * per, c_hi = min(KC, c_lo + per);
+  const int perw = ((max(c_hi - c_lo, 0) + 3) / 4 + ev) & ~ev, w_lo = c_lo + w * perw,
+            w_hi = min(c_hi, w_lo + perw);
+  const uint4* wsrc = a.wp + (size_t)nb * (W8 ? KC / 2 : KC) * 64 + lane;
   const uint4* xsrc = a.xp + lane;
   const int lo8 = 2 * c_lo, n8 = 2 * max(c_hi - c_lo, 0);  // this workgroup's k/8 range
 
@@ -303,7 +325,8 @@ __global__ __launch_bounds__(256, XMODE == X_NORM8 ? 2 : 3) void gemm_few_kernel
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int cc = max(min(c + u, w_hi - 1), 0);
-      b[u] = wsrc[(size_t)cc * 64];
+      if constexpr (!W8) b[u] = wsrc[(size_t)cc * 64];
+      else if (u < U / 2) b[u] = wsrc[(size_t)max(min((c >> 1) + u, (w_hi >> 1) - 1), 0) * 64];
       if constexpr (XMODE == X_GLOBAL) {
         const uint4* xs = (c + u < w_hi) ? xsrc + (size_t)cc * 64 : a.zero_tile + lane;
         x[u] = *xs;
@@ -321,7 +344,10 @@ __global__ __launch_bounds__(256, XMODE == X_NORM8 ? 2 : 3) void gemm_few_kernel
       }
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) acc = mfma32<F16>(b[u], x[u], acc);
+    for (int u = 0; u < U; ++u) {
+      if constexpr (W8) acc = mfma32<F16>(e4m3_slot_half(b[u >> 1], u & 1), x[u], acc);
+      else acc = mfma32<F16>(b[u], x[u], acc);
+    }
   };
 
   // Loads return in issue order: row 0, the gains and the first two splits of its partial
@@ -437,6 +463,7 @@ __global__ __launch_bounds__(256, XMODE == X_NORM8 ? 2 : 3) void gemm_few_kernel
   if (w > 0) return;
 #pragma unroll
   for (int i = 0; i < 16; ++i) acc[i] += red[0][i][lane] + red[1][i][lane] + red[2][i][lane];
+  if constexpr (W8) scale_tile(a.wscale, nb, lane >> 5, acc);
 
   if (EPI == EPI_RESID && a.S > 1 && a.e.defer_split) {
     // the split's partial rows [split][row][feature] are left for the consumer (the
@@ -484,10 +511,13 @@ __global__ __launch_bounds__(256, XMODE == X_NORM8 ? 2 : 3) void gemm_few_kernel
 
 template <int MT, int EPI>
 static hipError_t set_attr() {
-  hipError_t e = hipFuncSetAttribute((const void*)gemm_rows_kernel<MT, EPI, false>,
+  hipError_t e = hipFuncSetAttribute((const void*)gemm_rows_kernel<MT, EPI, false, false>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, 2 * MT * 4096);
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute((const void*)gemm_rows_kernel<MT, EPI, true>,
+  e = hipFuncSetAttribute((const void*)gemm_rows_kernel<MT, EPI, true, false>,
+                          hipFuncAttributeMaxDynamicSharedMemorySize, 2 * MT * 4096);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute((const void*)gemm_rows_kernel<MT, EPI, true, true>,
                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * MT * 4096);
 }
 
@@ -503,39 +533,39 @@ int gemm_init() {
   return 0;
 }
 
-template <int MT, bool F16>
+template <int MT, bool F16, bool W8>
 static void launch_mt(int epi, const GemmArgs& a, int grid, hipStream_t st) {
   const size_t shm = (size_t)2 * MT * 4096;
   switch (epi) {
     case EPI_QKV:
-      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_QKV, F16>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_QKV, F16, W8>), dim3(grid), dim3(256), shm, st, a);
       break;
     case EPI_RESID:
-      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_RESID, F16>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_RESID, F16, W8>), dim3(grid), dim3(256), shm, st, a);
       break;
     case EPI_SWIGLU:
-      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_SWIGLU, F16>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_SWIGLU, F16, W8>), dim3(grid), dim3(256), shm, st, a);
       break;
     default:
-      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_LOGITS, F16>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_rows_kernel<MT, EPI_LOGITS, F16, W8>), dim3(grid), dim3(256), shm, st, a);
       break;
   }
 }
 
-template <bool F16, int XMODE>
+template <bool F16, int XMODE, bool W8>
 static void launch_few(int epi, const GemmArgs& a, int grid, size_t shm, hipStream_t st) {
   switch (epi) {
     case EPI_QKV:
-      hipLaunchKernelGGL((gemm_few_kernel<EPI_QKV, F16, XMODE>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_QKV, F16, XMODE, W8>), dim3(grid), dim3(256), shm, st, a);
       break;
     case EPI_RESID:
-      hipLaunchKernelGGL((gemm_few_kernel<EPI_RESID, F16, XMODE>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_RESID, F16, XMODE, W8>), dim3(grid), dim3(256), shm, st, a);
       break;
     case EPI_SWIGLU:
-      hipLaunchKernelGGL((gemm_few_kernel<EPI_SWIGLU, F16, XMODE>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_SWIGLU, F16, XMODE, W8>), dim3(grid), dim3(256), shm, st, a);
       break;
     default:
-      hipLaunchKernelGGL((gemm_few_kernel<EPI_LOGITS, F16, XMODE>), dim3(grid), dim3(256), shm, st, a);
+      hipLaunchKernelGGL((gemm_few_kernel<EPI_LOGITS, F16, XMODE, W8>), dim3(grid), dim3(256), shm, st, a);
       break;
   }
 }
@@ -552,11 +582,13 @@ bool gemm_can_fuse_norm(int n_rows_host, int decode_pos, int kpad) {
 // matrix-core bound and go to the kernel built for that.
 static const int kTallRows = 1024;
 
-int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, const bf16_t* xp,
+int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, const float* wscale, int n_blocks, int kpad,
+                const bf16_t* xp,
                  const int* n_rows, int n_rows_host, int rows_cap, const GemmEpi& e, hipStream_t st,
                  const NormIn* norm) {
   GemmArgs a;
   a.wp = (const uint4*)wp;
+  a.wscale = c->w8 ? wscale : nullptr;
   a.xp = (const uint4*)xp;
   a.zero_tile = (const uint4*)c->zero_tile;
   a.NB = n_blocks;
@@ -584,17 +616,21 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, 
     a.P = n_blocks * S;
     if (norm) {  // only offered when gemm_can_fuse_norm() holds
       // LDS for the normalised rows: this workgroup's share of K, [k/8][row] 16-byte slices
-      const size_t shm = (size_t)(2 * ((KC + S - 1) / S)) * n_rows_host * 16;
+      const int per = ((KC + S - 1) / S + (c->w8 ? 1 : 0)) & ~(c->w8 ? 1 : 0);  // as in the kernel
+      const size_t shm = (size_t)(2 * per) * n_rows_host * 16;
       if (norm->d <= 4096) {
-        if (c->f16) launch_few<true, X_NORM4>(epi, a, a.P, shm, st);
-        else launch_few<false, X_NORM4>(epi, a, a.P, shm, st);
+        if (c->w8) launch_few<true, X_NORM4, true>(epi, a, a.P, shm, st);
+        else if (c->f16) launch_few<true, X_NORM4, false>(epi, a, a.P, shm, st);
+        else launch_few<false, X_NORM4, false>(epi, a, a.P, shm, st);
       } else {
-        if (c->f16) launch_few<true, X_NORM8>(epi, a, a.P, shm, st);
-        else launch_few<false, X_NORM8>(epi, a, a.P, shm, st);
+        if (c->w8) launch_few<true, X_NORM8, true>(epi, a, a.P, shm, st);
+        else if (c->f16) launch_few<true, X_NORM8, false>(epi, a, a.P, shm, st);
+        else launch_few<false, X_NORM8, false>(epi, a, a.P, shm, st);
       }
     } else {
-      if (c->f16) launch_few<true, X_GLOBAL>(epi, a, a.P, 0, st);
-      else launch_few<false, X_GLOBAL>(epi, a, a.P, 0, st);
+      if (c->w8) launch_few<true, X_GLOBAL, true>(epi, a, a.P, 0, st);
+      else if (c->f16) launch_few<true, X_GLOBAL, false>(epi, a, a.P, 0, st);
+      else launch_few<false, X_GLOBAL, false>(epi, a, a.P, 0, st);
     }
   } else if (rows_cap >= kTallRows) {
     launch_gemm_tall(c->f16, epi, a, rows_cap, st);
@@ -622,8 +658,9 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, int n_blocks, int kpad, 
     a.S = S;
     a.P = tiles * S;
     const int grid = ((a.P + 7) / 8) * 8 * a.MB;
-    if (c->f16) launch_mt<MT, true>(epi, a, grid, st);
-    else launch_mt<MT, false>(epi, a, grid, st);
+    if (c->w8) launch_mt<MT, true, true>(epi, a, grid, st);
+    else if (c->f16) launch_mt<MT, true, false>(epi, a, grid, st);
+    else launch_mt<MT, false, false>(epi, a, grid, st);
   }
   if (timed) {
     (void)hipEventRecord(c->prof_stop[c->prof_n], st);

@@ -3,7 +3,8 @@
 #include "common.h"
 
 struct GemmArgs {
-  const uint4* wp;    // weights, fragment order, 64 uint4 per tile
+  const uint4* wp;    // weights, fragment order, 64 uint4 per tile (e4m3 codes: per two tiles)
+  const float* wscale;  // e4m3 weights: scale per output feature (packed row order), else null
   const uint4* xp;    // activations, fragment order
   const uint4* zero_tile;  // 1 KiB of zeros
   NormIn norm;        // fused RMSNorm of the input rows (few-rows kernel only)
@@ -16,6 +17,33 @@ struct GemmArgs {
   int* counters;
   GemmEpi e;
 };
+
+// e4m3 weights: a lane's 8 codes of one k-tile (two dwords) -> its 8 fp16 operand values.
+// The hardware conversion decodes OCP e4m3 (verified code by code); every e4m3 value is an
+// fp16 value, so the second conversion is exact.
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+template <bool HIGH>
+__device__ inline uint32_t e4m3_pair_to_f16(uint32_t codes) {
+  const f32x2_t v = __builtin_amdgcn_cvt_pk_f32_fp8((int)codes, HIGH);
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(v.x, v.y));
+}
+__device__ inline uint4 e4m3_tile_to_f16(uint32_t lo, uint32_t hi) {
+  return make_uint4(e4m3_pair_to_f16<false>(lo), e4m3_pair_to_f16<true>(lo),
+                    e4m3_pair_to_f16<false>(hi), e4m3_pair_to_f16<true>(hi));
+}
+// k-tile (2 c + half) of a 16-byte slot that holds the codes of two k-tiles
+__device__ inline uint4 e4m3_slot_half(const uint4& slot, int half) {
+  return half ? e4m3_tile_to_f16(slot.z, slot.w) : e4m3_tile_to_f16(slot.x, slot.y);
+}
+// the scales of the 16 results a lane holds of weight block nb (features 8 q + 4 g + i)
+__device__ inline void scale_tile(const float* wscale, int nb, int g, f32x16& acc) {
+#pragma unroll
+  for (int q4 = 0; q4 < 4; ++q4) {
+    const float4 s = *(const float4*)(wscale + nb * 32 + 8 * q4 + 4 * g);
+    acc[4 * q4] *= s.x; acc[4 * q4 + 1] *= s.y; acc[4 * q4 + 2] *= s.z; acc[4 * q4 + 3] *= s.w;
+  }
+}
 
 __device__ inline float silu_f(float x) { return x / (1.f + __expf(-x)); }
 

@@ -500,6 +500,120 @@ void launch_pack(bool to_f16, const bf16_t* src, int N, int K, bf16_t* dst, int 
                      kpad, mode, p0, p1, p2, to_f16 ? 1 : 0);
 }
 
+// ---------------------------------------------------------------------------
+// Weight-only e4m3 storage.  Scale of a row: the smallest power of two s with
+// max|w_row| / s <= 448 (the largest e4m3 value), 1 for a zero row, never below 2^-120.
+// Codes: round to nearest representable value, ties to the even mantissa.
+// ---------------------------------------------------------------------------
+__device__ inline float bf16_val(bf16_t x) { return __uint_as_float((uint32_t)x << 16); }
+// 1 / s for a power of two s, by its exponent field
+__device__ inline float pow2_inverse(float s) { return __uint_as_float((254u - (__float_as_uint(s) >> 23)) << 23); }
+
+// OCP e4m3 code of x, |x| <= 448: below the smallest normal 2^-6 the values are the
+// multiples of 2^-9 (rintf rounds to nearest even); above, the fp32 mantissa is rounded
+// to 3 bits in the integer domain, which carries into the exponent by itself.
+__device__ inline uint32_t e4m3_encode(float x) {
+  const uint32_t sign = (__float_as_uint(x) >> 24) & 0x80u;
+  const float a = fabsf(x);
+  uint32_t code;
+  if (a < 0.015625f) {
+    code = (uint32_t)rintf(a * 512.f);  // 0 .. 8; 8 is the code of 2^-6
+  } else {
+    uint32_t v = __float_as_uint(a);
+    v += 0x7ffffu + ((v >> 20) & 1u);
+    code = (v >> 20) - ((127u - 7u) << 3);  // (exponent field - 120) << 3 | mantissa
+    if (code > 126u) code = 126u;
+  }
+  return code | sign;
+}
+
+__global__ __launch_bounds__(256) void row_scales_kernel(const bf16_t* __restrict__ src, int N, int K,
+                                                         float* __restrict__ scales) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= N) return;
+  float m = 0.f;
+  for (int k = lane; k < K; k += 64) m = fmaxf(m, fabsf(bf16_val(src[(size_t)row * K + k])));
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+  if (lane == 0) {
+    float s = 1.f;
+    if (m > 0.f) {
+      // m = f * 2^E, 1 <= f < 2:  f * 2^(E - e) <= 1.75 * 2^8  <=>  e >= E - 8 (f <= 1.75) or E - 7
+      const uint32_t u = __float_as_uint(m);
+      int E = (int)(u >> 23) - 127;
+      const uint32_t frac = u & 0x7fffffu;
+      if ((u >> 23) == 0) E = -127;  // (fp32 subnormal: far below the floor anyway)
+      int e = E - 8 + (frac > 0x600000u ? 1 : 0);  // 0x600000 = .75
+      if (e < -120) e = -120;
+      s = __uint_as_float((uint32_t)(e + 127) << 23);
+    }
+    scales[row] = s;
+  }
+}
+
+void launch_row_scales(const bf16_t* src, int N, int K, float* scales, hipStream_t st) {
+  hipLaunchKernelGGL(row_scales_kernel, dim3((N + 3) / 4), dim3(256), 0, st, src, N, K, scales);
+}
+
+__global__ __launch_bounds__(256) void quantize_e4m3_kernel(const bf16_t* __restrict__ src, int N, int K,
+                                                            const float* __restrict__ scales,
+                                                            uint8_t* __restrict__ codes) {
+  const size_t n = (size_t)N * K;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const float inv = pow2_inverse(scales[i / K]);
+    codes[i] = (uint8_t)e4m3_encode(bf16_val(src[i]) * inv);
+  }
+}
+
+void launch_quantize_e4m3(const bf16_t* src, int N, int K, const float* scales, uint8_t* codes,
+                          hipStream_t st) {
+  hipLaunchKernelGGL(quantize_e4m3_kernel, dim3(1024), dim3(256), 0, st, src, N, K, scales, codes);
+}
+
+// Codes in fragment order: a 16-byte lane slot holds the lane's 8 codes of k-tile 2c and
+// its 8 codes of k-tile 2c + 1 (lane = (row % 32) + 32 * ((col % 16) / 8) as for the 16-bit
+// operands), so one 1 KiB wave load brings two k-tiles.  Row permutation as pack_weights_kernel.
+__global__ __launch_bounds__(256) void pack_e4m3_kernel(const bf16_t* __restrict__ src, int N, int K,
+                                                        const float* __restrict__ scales,
+                                                        bf16_t* __restrict__ dst, float* __restrict__ scales_packed,
+                                                        int n_pack, int kpad, int mode, int p0, int p1, int p2) {
+  const int KC2 = kpad / 32;
+  const size_t n_chunks = (size_t)(n_pack / 32) * KC2 * 64;  // 16-byte chunks
+  for (size_t c = (size_t)blockIdx.x * 256 + threadIdx.x; c < n_chunks; c += (size_t)gridDim.x * 256) {
+    const int lane = (int)(c & 63);
+    const size_t tile = c >> 6;
+    const int kc2 = (int)(tile % KC2), rt = (int)(tile / KC2);
+    const int pr = rt * 32 + (lane & 31);
+    const int sr = pack_src_row(pr, mode, p0, p1, p2);
+    uint32_t out[4] = {0, 0, 0, 0};
+    if (sr < N) {
+      const float inv = pow2_inverse(scales[sr]);
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int col = (2 * kc2 + h) * 16 + 8 * (lane >> 5);
+        if (col < K) {  // K is a multiple of 8
+          const uint4 v = *(const uint4*)(src + (size_t)sr * K + col);
+          const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = e4m3_encode(__uint_as_float(u[i] << 16) * inv);
+            const uint32_t hi = e4m3_encode(__uint_as_float(u[i] & 0xffff0000u) * inv);
+            out[2 * h + (i >> 1)] |= (lo | (hi << 8)) << (16 * (i & 1));
+          }
+        }
+      }
+    }
+    *(uint4*)((char*)dst + c * 16) = make_uint4(out[0], out[1], out[2], out[3]);
+    if (kc2 == 0 && lane < 32) scales_packed[pr] = sr < N ? scales[sr] : 1.f;
+  }
+}
+
+void launch_pack_e4m3(const bf16_t* src, int N, int K, const float* scales, bf16_t* dst, float* scales_packed,
+                      int n_pack, int kpad, int mode, int p0, int p1, int p2, hipStream_t st) {
+  hipLaunchKernelGGL(pack_e4m3_kernel, dim3(2048), dim3(256), 0, st, src, N, K, scales, dst, scales_packed,
+                     n_pack, kpad, mode, p0, p1, p2);
+}
+
 __global__ void bf16_to_f32_kernel(const bf16_t* __restrict__ src, float* __restrict__ dst, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) dst[i] = __uint_as_float((uint32_t)src[i] << 16);

@@ -7,14 +7,21 @@ import synth
 from oracle import vlac_oracle as O
 
 
-def oracle_model(cfg, seed, gain_jitter=0.1, std=0.02, dtype=np.float64, cache_layers=True):
-    """Oracle Model over synth weights (bf16 values upcast)."""
+def oracle_model(cfg, seed, gain_jitter=0.1, std=0.02, dtype=np.float64, cache_layers=True, w8=False):
+    """Oracle Model over synth weights (bf16 values upcast).  w8: every weight matrix is
+    replaced by what weight-only e4m3 storage keeps of it (the oracle's own quantiser)."""
+    from oracle import fp8 as Q
+
+    def keep(k, v):
+        v = v.float().numpy()
+        return Q.quantize_rows(v)[2].astype(np.float32) if w8 and k.startswith("w") else v
+
     def layer(l):
-        return {k: v.float().numpy() for k, v in
+        return {k: keep(k, v) for k, v in
                 synth.make_layer(cfg, seed, l, std=std, gain_jitter=gain_jitter).items()}
     if cache_layers:
         layer = functools.lru_cache(maxsize=None)(layer)
-    head = {k: v.float().numpy() for k, v in
+    head = {k: keep(k, v) for k, v in
             synth.make_head(cfg, seed, std=std, gain_jitter=gain_jitter).items()}
     return O.Model(cfg, layer, head, dtype=dtype)
 
