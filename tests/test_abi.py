@@ -52,7 +52,7 @@ def test_create_rejects_bad_shapes_on_the_host():
                      (dict(vocab=100), -2), (dict(max_seq=100), -2), (dict(n_q_heads=6), -2),
                      (dict(n_q_heads=8, n_kv_heads=3), -2), (dict(n_layers=0), -3),
                      (dict(max_batch=0), -3), (dict(max_seq=1 << 20), -3), (dict(rms_eps=0.0), -3),
-                     (dict(rope_base=1.0), -3), (dict(operand_dtype=2), -3)):
+                     (dict(rope_base=1.0), -3), (dict(operand_dtype=3), -3)):
         cfg = good_cfg(**kw)
         assert lib.vlac_create(C.byref(cfg), C.byref(out)) == want, kw
         assert V.vlac_kv_cache_bytes(cfg) == 0
