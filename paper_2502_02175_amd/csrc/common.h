@@ -55,15 +55,23 @@ __device__ inline uint32_t pack_op2(float lo, float hi) {
 // (__threadfence) writes back and invalidates a whole L2, which costs more than
 // the kernels it would sit in.  Instead the few words that change hands are
 // written and read with agent-scope atomic accesses, which go through to the
-// memory side and bypass stale lines; a workgroup-scope fence (a plain wait for
-// outstanding stores) orders them before the arrival counter is bumped.
+// memory side and bypass stale lines.  Before the arrival counter is bumped, every wave
+// waits until its stores have been acknowledged (s_waitcnt vmcnt(0), stores count there
+// on this chip): the workgroup-scope fence that follows does NOT wait for them by itself
+// (the waves of a workgroup share their L1, so the compiler omits the wait), and without
+// it the counter can overtake a store on its way to another L2 channel: the last
+// workgroup to arrive then reads what the location held before (seen about once in 400
+// prefills of 224 launches each).
 __device__ inline void st_coherent(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ inline float ld_coherent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ inline void stores_done() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+__device__ inline void stores_done() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+}
 
 // D[32x32] += A[32x16] . B[16x32]; a lane supplies 8 consecutive k of row/col (lane % 32)
 template <bool F16>

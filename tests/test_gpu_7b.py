@@ -130,6 +130,24 @@ def test_7b_full_depth_properties():
         gm.close()
 
 
+def test_split_k_hand_over_is_reproducible():
+    """The same sparse prefills 400 times over at full depth: every one reproduces the full
+    recompute bit for bit.  (Partial sums that a workgroup parks for the last one to arrive
+    must have reached the memory side before the arrival counter moves; when the wait for
+    that was missing, about one prefill in 400 read a stale partial tile.)"""
+    prev, cur, redrawn, e_prev, e_cur = inputs(seed=2)
+    gm = GpuModel(CFG, seed=2, max_batch=1, max_seq=320, gain_jitter=0.1, gen_device="cuda:0")
+    try:
+        full = gm.prefill(e_cur[None], N_VIS, want_stats=False, want_hidden=False)["logits"]
+        assert np.isfinite(full).all()
+        for it in range(50):
+            for k in (256, 240, 179, 150, 100, 40, 20, 0):
+                part = gm.prefill(e_cur[None], N_VIS, [list(range(k))], want_stats=False, want_hidden=False)
+                assert np.array_equal(part["logits"], full), (it, k)
+    finally:
+        gm.close()
+
+
 def _random_streams(cfg, B, n_vis, n_txt, static_frac, seed):
     """Embeddings of two consecutive steps for B streams: a fraction of the visual
     tokens keeps its embedding, the rest is re-drawn."""
