@@ -137,6 +137,34 @@ def test_batched_streams_gqa_ragged(operand):
         gm.close()
 
 
+def test_long_text_statistic_by_last_arriver():
+    """130 text tokens (more than the 96 the deferred reduction of the attention statistic
+    provides for): the per-layer reduction by the last workgroup to arrive serves instead.
+    Full and sparse step, two streams with different reuse sets."""
+    cfg = TINY
+    om = oracle_model(cfg, seed=11, std=0.05)
+    gm = GpuModel(cfg, seed=11, max_batch=2, max_seq=192, std=0.05)
+    try:
+        rng = np.random.default_rng(4)
+        n_vis, n_txt, B = 40, 130, 2
+        e0 = synth.round_bf16(rng.standard_normal((B, n_vis + n_txt, cfg.d_model)))
+        e1 = e0.copy()
+        e1[:, 5:20] = synth.round_bf16(rng.standard_normal((B, 15, cfg.d_model)))
+        caches = [O.new_cache(cfg, 192) for _ in range(B)]
+        want0 = [O.dense_forward(om, e0[b], n_vis, caches[b]) for b in range(B)]
+        got0 = gm.prefill(e0, n_vis)
+        for b in range(B):
+            check(got0, want0[b], b)
+        reuse = [[0, 1, 2, 3, 4] + list(range(20, 40)), [30, 31, 2]]
+        want1 = [O.sparse_forward(om, e1[b], n_vis, caches[b], [reuse[b]] * cfg.n_layers) for b in range(B)]
+        for rep in range(3):     # the arrival counters start every launch from zero
+            got1 = gm.prefill(e1, n_vis, reuse)
+            for b in range(B):
+                check(got1, want1[b], b)
+    finally:
+        gm.close()
+
+
 def test_mid_size_split_k_with_layer_varying_reuse():
     """d = 1024: the projection GEMMs split K over workgroups and hand partial rows to the
     next row kernel; with reuse counts that grow over depth the row lists of consecutive
