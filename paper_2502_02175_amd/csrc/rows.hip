@@ -237,7 +237,10 @@ __global__ __launch_bounds__(256) void resid_norm_rows_kernel(
   const float* p0 = part + (size_t)pslot * d;
   const size_t pstride = (size_t)part_rows * d;
   const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-  float4 v[MAXI], g[MAXI], t0[MAXI], t1[MAXI];
+  // NS splits are in flight at a time (all 8 for rows of up to 4096 elements): a split past
+  // the last one is loaded from the last (a valid address, no branch) and not added
+  constexpr int NS = MAXI <= 4 ? 8 : 4;
+  float4 v[MAXI], g[MAXI], t[NS][MAXI];
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) {
     const int k = tid * 4 + i * 1024;
@@ -247,21 +250,23 @@ __global__ __launch_bounds__(256) void resid_norm_rows_kernel(
       if (gain) g[i] = *(const float4*)(gain + k);
     }
   }
-  for (int s = 0; s < S; s += 2) {  // fixed order
+  for (int s = 0; s < S; s += NS) {  // fixed order
 #pragma unroll
-    for (int i = 0; i < MAXI; ++i) {
-      const int k = tid * 4 + i * 1024;
-      t0[i] = t1[i] = zero;
-      if (k < d) {
-        t0[i] = *(const float4*)(p0 + (size_t)s * pstride + k);
-        if (s + 1 < S) t1[i] = *(const float4*)(p0 + (size_t)(s + 1) * pstride + k);
+    for (int u = 0; u < NS; ++u)
+#pragma unroll
+      for (int i = 0; i < MAXI; ++i) {
+        const int k = tid * 4 + i * 1024;
+        t[u][i] = zero;
+        if (k < d) t[u][i] = *(const float4*)(p0 + (size_t)min(s + u, S - 1) * pstride + k);
       }
-    }
 #pragma unroll
-    for (int i = 0; i < MAXI; ++i) {
-      v[i].x += t0[i].x; v[i].y += t0[i].y; v[i].z += t0[i].z; v[i].w += t0[i].w;
-      v[i].x += t1[i].x; v[i].y += t1[i].y; v[i].z += t1[i].z; v[i].w += t1[i].w;
-    }
+    for (int u = 0; u < NS; ++u)
+#pragma unroll
+      for (int i = 0; i < MAXI; ++i) {
+        const float on = s + u < S ? 1.f : 0.f;
+        v[i].x += on * t[u][i].x; v[i].y += on * t[u][i].y;
+        v[i].z += on * t[u][i].z; v[i].w += on * t[u][i].w;
+      }
   }
   float ss = 0.f;
 #pragma unroll
