@@ -43,6 +43,7 @@ struct AttnArgs {
   int TT, lv_pad;
   int* stat_counters;   // [B]
   int defer_stats;      // the parked sums are added up by stats_reduce_kernel after the last layer
+  int rows4_from;       // > 0: streams with at least this many rows are left to attn_rows4_kernel
 };
 
 template <int HD, bool F16>
@@ -60,6 +61,7 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a) {
   const int n_b = dec ? 1 : a.slot_off[b + 1] - off_b;
   const int s0 = blockIdx.x * 32;
   if (s0 >= n_b) return;
+  if (a.rows4_from > 0 && n_b >= a.rows4_from) return;
   const int hk = h / (a.n_q_heads / a.n_kv_heads);
   const bool valid = s0 + j < n_b;
   const int sg = off_b + (valid ? s0 + j : n_b - 1);  // this lane's query slot
@@ -254,6 +256,183 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// The same attention for MANY query tiles per stream (long sequences, many streams): one
+// query tile per WAVE.  The 4 waves of a workgroup walk the key tiles together and share
+// every K and V tile through LDS (fragment order is kept, a tile is copied 16 bytes per
+// thread as it lies), so a stream's cache is read once per 128 queries instead of once per
+// 32, and there is nothing to merge.  A wave skips the key tiles behind its last query.
+// The statistic is parked for stats_reduce_kernel (this kernel is only used where that
+// reduction applies): waves that hold text rows run the second pass over the vision keys,
+// whose K tiles the workgroup stages the same way.
+// ---------------------------------------------------------------------------
+template <int HD, bool F16>
+__global__ __launch_bounds__(256) void attn_rows4_kernel(AttnArgs a) {
+  constexpr int NC = HD / 16;      // k-tiles of a head
+  constexpr int NI = HD / 32;      // feature blocks of a head
+  constexpr int TILE = NC * 64;    // 16-byte chunks of a K tile (and of a V tile)
+  constexpr int PER = TILE / 256;  // chunks per thread
+  __shared__ uint4 kvs[2][2][TILE];  // [buffer][K, V]
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int j = lane & 31, g = lane >> 5;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int off_b = a.slot_off[b];
+  const int n_b = a.slot_off[b + 1] - off_b;
+  if ((int)blockIdx.x * 128 >= n_b || n_b < a.rows4_from) return;
+  const int qt = blockIdx.x * 4 + w, s0 = qt * 32;  // this wave's query tile
+  const bool active = s0 < n_b;
+  const int hk = h / (a.n_q_heads / a.n_kv_heads);
+  const bool valid = active && s0 + j < n_b;
+  const int sg = off_b + (valid ? s0 + j : n_b - 1);  // this lane's query slot
+  const int pos = valid ? (a.rows[sg] & 0xffff) : 0;
+  const int pos_last = active ? (a.rows[off_b + min(s0 + 31, n_b - 1)] & 0xffff) : -1;
+  const int n_kt = (pos_last >> 5) + 1;  // 0 for a wave without queries
+  // rows ascend by position: the workgroup needs the key tiles of its last query
+  const int pos_wg = a.rows[off_b + min((int)blockIdx.x * 128 + 127, n_b - 1)] & 0xffff;
+  const int n_kt_wg = (pos_wg >> 5) + 1;
+
+  const size_t head_elems = (size_t)a.max_seq * HD;
+  const uint4* ksrc = (const uint4*)(a.kv + (size_t)b * a.kv_stream_stride + (size_t)hk * head_elems) + tid;
+  const uint4* vsrc = ksrc + (size_t)a.n_kv_heads * head_elems / 8;
+
+  uint4 qf[NC];
+  {
+    const bf16_t* qsrc = a.qbuf + ((size_t)(sg >> 5) * a.n_q_heads + h) * (size_t)NC * 512 +
+                         (size_t)(((sg & 31) + 32 * g) << 3);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) qf[c] = *(const uint4*)(qsrc + (size_t)c * 512);
+  }
+  f32x16 o[NI];
+#pragma unroll
+  for (int ib = 0; ib < NI; ++ib)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[ib][i] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  uint4 kr[PER], vr[PER];  // the next tile on its way to LDS
+#pragma unroll
+  for (int u = 0; u < PER; ++u) {
+    kvs[0][0][tid + 256 * u] = ksrc[256 * u];
+    kvs[0][1][tid + 256 * u] = vsrc[256 * u];
+  }
+  __syncthreads();
+  for (int kt = 0; kt < n_kt_wg; ++kt) {
+    const int buf = kt & 1;
+    const size_t nx = (size_t)min(kt + 1, n_kt_wg - 1) * TILE;
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      kr[u] = ksrc[nx + 256 * u];
+      vr[u] = vsrc[nx + 256 * u];
+    }
+    if (kt < n_kt) {
+      f32x16 s;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) s = mfma32<F16>(kvs[buf][0][c * 64 + lane], qf[c], s);
+      // register 4*q4 + e of a lane is key 32*kt + 8*q4 + 4*g + e
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int kp = 32 * kt + 8 * (i >> 2) + 4 * g + (i & 3);
+        s[i] = (kp <= pos) ? s[i] * a.scale_log2e : -INFINITY;
+        tmax = fmaxf(tmax, s[i]);
+      }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      const float m_new = fmaxf(m, tmax);
+      const float alpha = (m_new == -INFINITY) ? 1.f : exp2f(m - m_new);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      m = m_new;
+      float psum = 0.f;
+      float pr[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        pr[i] = exp2f(s[i] - m_use);
+        psum += pr[i];
+      }
+      l = l * alpha + psum;
+      uint4 pb[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        pb[t].x = pack_op2<F16>(pr[8 * t + 0], pr[8 * t + 1]);
+        pb[t].y = pack_op2<F16>(pr[8 * t + 2], pr[8 * t + 3]);
+        pb[t].z = pack_op2<F16>(pr[8 * t + 4], pr[8 * t + 5]);
+        pb[t].w = pack_op2<F16>(pr[8 * t + 6], pr[8 * t + 7]);
+      }
+#pragma unroll
+      for (int ib = 0; ib < NI; ++ib) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[ib][i] *= alpha;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) o[ib] = mfma32<F16>(kvs[buf][1][(ib * 2 + t) * 64 + lane], pb[t], o[ib]);
+      }
+    }
+    // the other buffer was last read in the step before this one, which every wave has left
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      kvs[buf ^ 1][0][tid + 256 * u] = kr[u];
+      kvs[buf ^ 1][1][tid + 256 * u] = vr[u];
+    }
+    __syncthreads();
+  }
+  l += __shfl_xor(l, 32);
+  const float inv = 1.f / l;  // (a wave without queries: never used)
+  if (valid) {
+#pragma unroll
+    for (int ib = 0; ib < NI; ++ib)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int f = h * HD + 32 * ib + 8 * q4 + 4 * g;
+        *(uint2*)(a.out + frag_off(sg, f, a.kc_out)) =
+            make_uint2(pack_op2<F16>(o[ib][4 * q4] * inv, o[ib][4 * q4 + 1] * inv),
+                       pack_op2<F16>(o[ib][4 * q4 + 2] * inv, o[ib][4 * q4 + 3] * inv));
+      }
+  }
+
+  // ---- text-to-vision statistic (the conditions up to the loop are uniform over the workgroup) ----
+  if (!a.attn_mean || a.L_t <= 0 || a.L_v <= 0) return;
+  if (pos_wg < a.L_v) return;  // no text row in this workgroup
+  const int x_first = (n_b - a.L_t) >> 5;  // first query tile that holds a text row
+  const bool text_wave = active && pos_last >= a.L_v;
+  const bool is_text = valid && pos >= a.L_v;
+  float* park = a.statp + (((size_t)b * a.n_q_heads + h) * a.TT + (qt - x_first)) * a.lv_pad;
+  const int n_vt = (a.L_v + 31) >> 5;
+  // (all waves are past their last read of the buffers: the loop ended on a barrier)
+#pragma unroll
+  for (int u = 0; u < PER; ++u) kvs[0][0][tid + 256 * u] = ksrc[256 * u];
+  __syncthreads();
+  for (int kt = 0; kt < n_vt; ++kt) {
+    const int buf = kt & 1;
+    const size_t nx = (size_t)min(kt + 1, n_vt - 1) * TILE;
+#pragma unroll
+    for (int u = 0; u < PER; ++u) kr[u] = ksrc[nx + 256 * u];
+    if (text_wave) {
+      f32x16 s;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) s = mfma32<F16>(kvs[buf][0][c * 64 + lane], qf[c], s);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        float pv = is_text ? exp2f(s[i] * a.scale_log2e - m) * inv : 0.f;
+        // sum over the 32 queries of the tile (the lanes of a half-wave), fixed order
+#pragma unroll
+        for (int d = 1; d < 32; d <<= 1) pv += __shfl_xor(pv, d);
+        s[i] = pv;
+      }
+      if (j == 0) {
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+          *(float4*)(park + 32 * kt + 8 * q4 + 4 * g) =
+              make_float4(s[4 * q4], s[4 * q4 + 1], s[4 * q4 + 2], s[4 * q4 + 3]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < PER; ++u) kvs[buf ^ 1][0][tid + 256 * u] = kr[u];
+    __syncthreads();
+  }
+}
+
 // The statistic of all layers at once, after the last layer (text-to-vision attention
 // averaged over heads and text queries, Eq. avistext): adds the sums that the attention
 // kernels of the prefill parked, [layer][B][Hq][TT][lv_pad], over heads and text tiles in
@@ -333,6 +512,26 @@ void launch_attention(vlac_ctx* c, int layer, int B, int rows_cap_per_stream, in
     a.statp = c->statp;
   }
   a.stat_counters = c->stat_counters;
+  // Long sequences of many streams (work for every CU several times over): streams with at
+  // least 256 rows to recompute go to the kernel with one query tile per WAVE, where the 4
+  // waves of a workgroup share K and V; streams with fewer rows (and every other shape) to the
+  // kernel with one query tile per workgroup and the key tiles dealt to its waves, which has
+  // the shorter critical path.  The row counts are known on the device only, so both
+  // kernels are launched and each leaves the other's streams alone.
+  const int groups = (rows_cap_per_stream + 127) / 128;
+  a.rows4_from = 0;
+  if (decode_pos < 0 && rows_cap_per_stream >= 512 && (long long)groups * m.n_q_heads * B >= 512 &&
+      (!a.attn_mean || a.defer_stats)) {
+    a.rows4_from = 256;
+    dim3 grid4(groups, m.n_q_heads, B);
+    if (m.head_dim == 128) {
+      if (c->f16) hipLaunchKernelGGL((attn_rows4_kernel<128, true>), grid4, dim3(256), 0, st, a);
+      else hipLaunchKernelGGL((attn_rows4_kernel<128, false>), grid4, dim3(256), 0, st, a);
+    } else {
+      if (c->f16) hipLaunchKernelGGL((attn_rows4_kernel<64, true>), grid4, dim3(256), 0, st, a);
+      else hipLaunchKernelGGL((attn_rows4_kernel<64, false>), grid4, dim3(256), 0, st, a);
+    }
+  }
   dim3 grid((rows_cap_per_stream + 31) / 32, m.n_q_heads, B);
   if (m.head_dim == 128) {
     if (c->f16) hipLaunchKernelGGL((attn_rows_kernel<128, true>), grid, dim3(256), 0, st, a);

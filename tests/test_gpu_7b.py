@@ -203,6 +203,14 @@ def test_hires_batched_shape_against_oracle():
     _check_streams(CFG.with_layers(1), B=2, n_vis=1024, n_txt=32, static_frac=0.7, seed=3, n_new=1)
 
 
+def test_hires_batched_streams_with_few_and_many_rows():
+    """The same shape with one stream 70% static (339 rows to recompute) and one 93% static
+    (about 100 rows): the two attention kernels for long sequences (one query tile per wave
+    for streams with many rows, one per workgroup for the others) share a launch pair."""
+    _check_streams(CFG.with_layers(1), B=2, n_vis=1024, n_txt=32, static_frac=np.array([[0.7], [0.93]]),
+                   seed=13, n_new=1)
+
+
 def test_gqa_batched_shape_against_oracle():
     """Grouped-query shape: d 1536, 12 query / 2 kv heads x 128, FFN 8960, rope base 1e6,
     256 visual + 48 text tokens, 75% static; 8 streams x 2 layers against the oracle."""
