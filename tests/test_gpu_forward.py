@@ -165,6 +165,38 @@ def test_long_text_statistic_by_last_arriver():
         gm.close()
 
 
+def test_many_long_streams_head_dim_64():
+    """32 streams of 512 + 32 tokens at the tiny layer shape (head_dim 64): long sequences of
+    many streams, where streams with at least 256 rows to recompute take the attention kernel
+    with one query tile per wave and the others the one with one query tile per workgroup.
+    Half of the streams are 40% static, the others 90%."""
+    cfg = TINY
+    B, n_vis, n_txt = 32, 512, 32
+    L = n_vis + n_txt
+    om = oracle_model(cfg, seed=12, std=0.05)
+    gm = GpuModel(cfg, seed=12, max_batch=B, max_seq=576, std=0.05)
+    try:
+        rng = np.random.default_rng(6)
+        e0 = synth.round_bf16(rng.standard_normal((B, L, cfg.d_model)))
+        e1 = e0.copy()
+        frac = np.where(np.arange(B) % 2 == 0, 0.4, 0.9)[:, None]
+        changed = rng.random((B, n_vis)) >= frac
+        e1[:, :n_vis][changed] = synth.round_bf16(rng.standard_normal((int(changed.sum()), cfg.d_model)))
+        caches = [O.new_cache(cfg, 576) for _ in range(B)]
+        want0 = [O.dense_forward(om, e0[b], n_vis, caches[b]) for b in range(B)]
+        got0 = gm.prefill(e0, n_vis)
+        for b in range(B):
+            check(got0, want0[b], b)
+        reuse = [np.flatnonzero(~changed[b]).tolist() for b in range(B)]
+        assert min(L - len(r) for r in reuse) < 128 and max(L - len(r) for r in reuse) > 256
+        want1 = [O.sparse_forward(om, e1[b], n_vis, caches[b], [reuse[b]] * cfg.n_layers) for b in range(B)]
+        got1 = gm.prefill(e1, n_vis, reuse)
+        for b in range(B):
+            check(got1, want1[b], b)
+    finally:
+        gm.close()
+
+
 def test_mid_size_split_k_with_layer_varying_reuse():
     """d = 1024: the projection GEMMs split K over workgroups and hand partial rows to the
     next row kernel; with reuse counts that grow over depth the row lists of consecutive
