@@ -74,6 +74,16 @@ def test_null_context_is_rejected():
                                    None, None) == -1
 
 
+def test_entry_points_beside_the_path_reject_null_arguments():
+    lib = V.lib()
+    assert lib.vlac_embed_patches(None, None, 1, 14, 14, 14, None, None, None, 1, None, None, 1, None) == -1
+    assert lib.vlac_quantize_e4m3(None, 4, 8, None, None, None) == -1
+    assert lib.vlac_profile_read2(None, None, None, None) == -1
+    assert lib.vlac_profile_bracket_cost(None, None, None) == -1
+    assert lib.vlac_select_static(None, None, None, 1, 14, 14, 14, 249, 250, 1, None, None, 0.5,
+                                  None, None, None, None, 1, None) == -1
+
+
 def test_no_cpu_fallback_without_gpu():
     import torch
     if torch.cuda.is_available():
