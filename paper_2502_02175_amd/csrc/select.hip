@@ -180,25 +180,30 @@ __global__ __launch_bounds__(256) void select_rank_kernel(
 }
 
 // grid (B).  Ascending list, count, and the list ordered by (score asc, index asc).
+// The kept tokens are compacted first (ascending index, with their scores, in LDS); the
+// place of a kept token in the reuse order is then the number of kept tokens that come
+// before it, counted over the compact list only: its k-th entry precedes the i-th if its
+// score is lower, or equal with k < i (the compact list ascends by index).
 __global__ __launch_bounds__(256) void select_compact_kernel(
     const uint8_t* __restrict__ flags, const float* __restrict__ relevance, int L_v,
     int32_t* __restrict__ out_idx, int32_t* __restrict__ out_order, int32_t* __restrict__ out_count,
     float* __restrict__ out_relevance, int stride) {
-  __shared__ float score[SEL_MAX_LV];
-  __shared__ uint8_t fl[SEL_MAX_LV];
+  __shared__ float cscore[SEL_MAX_LV];
+  __shared__ int cidx[SEL_MAX_LV];
   __shared__ int wsum[4];
   __shared__ int base_s;
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  for (int j = tid; j < L_v; j += 256) {
-    fl[j] = flags[(size_t)b * L_v + j];
-    score[j] = relevance[(size_t)b * L_v + j];
-    if (out_relevance) out_relevance[(size_t)b * L_v + j] = score[j];
-  }
   if (tid == 0) base_s = 0;
   __syncthreads();
   for (int c0 = 0; c0 < L_v; c0 += 256) {
     const int i = c0 + tid;
-    const int f = (i < L_v) ? fl[i] : 0;
+    int f = 0;
+    float sc = 0.f;
+    if (i < L_v) {
+      f = flags[(size_t)b * L_v + i];
+      sc = relevance[(size_t)b * L_v + i];
+      if (out_relevance) out_relevance[(size_t)b * L_v + i] = sc;
+    }
     const unsigned long long bal = __ballot(f);
     const int inwave = __popcll(bal & ((1ull << lane) - 1ull));
     if (lane == 0) wsum[w] = __popcll(bal);
@@ -207,18 +212,25 @@ __global__ __launch_bounds__(256) void select_compact_kernel(
     for (int k = 0; k < w; ++k) off += wsum[k];
     if (f) {
       const int k = off + inwave;
+      cidx[k] = i;
+      cscore[k] = sc;
       if (k < stride) out_idx[(size_t)b * stride + k] = i;
-      int ord = 0;
-      const float si = score[i];
-      for (int j = 0; j < L_v; ++j)
-        ord += fl[j] && ((score[j] < si) || (score[j] == si && j < i));
-      if (ord < stride) out_order[(size_t)b * stride + ord] = i;
     }
     __syncthreads();
     if (tid == 0) base_s += wsum[0] + wsum[1] + wsum[2] + wsum[3];
     __syncthreads();
   }
-  if (tid == 0) out_count[b] = base_s;
+  const int n = base_s;
+  if (tid == 0) out_count[b] = n;
+  for (int i = tid; i < n; i += 256) {
+    const float si = cscore[i];
+    int ord = 0;
+    for (int k = 0; k < n; ++k) {
+      const float sk = cscore[k];
+      ord += (sk < si) || (sk == si && k < i);
+    }
+    if (ord < stride) out_order[(size_t)b * stride + ord] = cidx[i];
+  }
 }
 
 void launch_select(const uint32_t* terms, int B, int L_v, int tau_num, int tau_den, int top_k,
@@ -242,37 +254,29 @@ void launch_select(const uint32_t* terms, int B, int L_v, int tau_num, int tau_d
 // Sec. 3.4.  grid (B), fp64 throughout; sums are fixed-shape trees, so the
 // result does not depend on scheduling.
 // ---------------------------------------------------------------------------
-__device__ inline double block_sum(double v, double* red) {
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  __syncthreads();
-  if (lane == 0) red[w] = v;
-  __syncthreads();
-  return red[0] + red[1] + red[2] + red[3];
-}
-
 #define RATIO_MAX_LAYERS 512
 
 __global__ __launch_bounds__(256) void layer_ratio_kernel(
     const float* __restrict__ attn_mean, int n_layers, int B, int L_v, float gain_k,
     const int32_t* __restrict__ reuse_count, float* __restrict__ out_alpha,
     int32_t* __restrict__ out_layer_count) {
-  __shared__ double red[4];
   __shared__ double ent[RATIO_MAX_LAYERS];
-  const int b = blockIdx.x, tid = threadIdx.x;
-  for (int l = 0; l < n_layers; ++l) {
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  // a wave per layer (layers w, w + 4, ...): its sums are shuffle trees of fixed shape
+  for (int l = w; l < n_layers; l += 4) {
     const float* a = attn_mean + ((size_t)l * B + b) * L_v;
     double s = 0;
-    for (int v = tid; v < L_v; v += 256) s += (double)a[v];
-    const double tot = block_sum(s, red);
+    for (int v = lane; v < L_v; v += 64) s += (double)a[v];
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    const double tot = s;
     double e = 0;
     if (tot > 0)
-      for (int v = tid; v < L_v; v += 256) {
+      for (int v = lane; v < L_v; v += 64) {
         const double p = (double)a[v] / tot;
         if (p > 0) e -= p * log(p);
       }
-    e = block_sum(e, red);
-    if (tid == 0) ent[l] = tot > 0 ? e : 0.0;
+    for (int o = 32; o > 0; o >>= 1) e += __shfl_xor(e, o);
+    if (lane == 0) ent[l] = tot > 0 ? e : 0.0;
   }
   __syncthreads();
   if (tid == 0) {
