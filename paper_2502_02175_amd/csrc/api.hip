@@ -133,6 +133,8 @@ int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out) {
   ctx->partial_floats = (size_t)64 << 20;  // 256 MiB of split-K workspace
   // partial rows of the projection + residual GEMMs: up to 8 splits of up to 1024 rows
   ctx->rpart_floats = (size_t)8 * (mr < 1024 ? mr : 1024) * m.d_model;
+  // (many rows: up to 3 splits of all rows)
+  if (mr >= 1024 && (size_t)3 * mr * m.d_model > ctx->rpart_floats) ctx->rpart_floats = (size_t)3 * mr * m.d_model;
   ctx->n_counters = 1 << 16;
   ctx->stat_tt = ms / 32 + 1;
 #define A_(ptr, n) if (e == hipSuccess) e = dalloc(&ctx->ptr, (size_t)(n))
@@ -492,7 +494,7 @@ void run_layer(vlac_ctx* c, int layer, int B, int rows_cap, int rows_cap_per_str
   if (*pending)
     launch_resid_norm_rows(c->f16, c->h, m.max_seq, c->rpart, *pending, rows_cap, c->h, m.max_seq,
                            rows, prev_slot, n_rows, n_host, rows_cap, W.g_attn, m.rms_eps,
-                           m.d_model, c->xa, kc_d, st);
+                           m.d_model, c->xa, kc_d, st, &c->pending_adapt);
   else
     launch_rmsnorm_rows(c->f16, resid_in, resid_stride, rows, n_rows, n_host, decode_pos, rows_cap,
                         W.g_attn, m.rms_eps, m.d_model, c->xa, kc_d, st);
@@ -503,10 +505,11 @@ void run_layer(vlac_ctx* c, int layer, int B, int rows_cap, int rows_cap_per_str
   e.resid_src = resid_in; e.resid_seq_stride = resid_stride;
   const int s_o = launch_gemm(c, EPI_RESID, W.wo, W.s_o, m.d_model / 32, c->kpad_q, c->xa, n_rows, n_host,
                               rows_cap, e, st);
+  const SplitAdapt ad_o = gemm_resid_adapt(c, m.d_model / 32, c->kpad_q, rows_cap, n_rows, n_host);
   if (rows_cap > 32 && s_o > 1)  // the few-rows kernel adds its splits up itself
     launch_resid_norm_rows(c->f16, resid_in, resid_stride, c->rpart, s_o, rows_cap, c->h, m.max_seq,
                            rows, nullptr, n_rows, n_host, rows_cap, W.g_ffn, m.rms_eps, m.d_model,
-                           c->xa, kc_d, st);
+                           c->xa, kc_d, st, &ad_o);
   else
     launch_rmsnorm_rows(c->f16, c->h, m.max_seq, rows, n_rows, n_host, decode_pos, rows_cap, W.g_ffn,
                         m.rms_eps, m.d_model, c->xa, kc_d, st);
@@ -515,6 +518,7 @@ void run_layer(vlac_ctx* c, int layer, int B, int rows_cap, int rows_cap_per_str
   const int s_d = launch_gemm(c, EPI_RESID, W.wdown, W.s_down, m.d_model / 32, c->kpad_f, c->xf, n_rows, n_host,
                               rows_cap, e, st);
   *pending = (rows_cap > 32 && s_d > 1) ? s_d : 0;
+  c->pending_adapt = gemm_resid_adapt(c, m.d_model / 32, c->kpad_f, rows_cap, n_rows, n_host);
 }
 
 // The residual rows of a decode pass with at most 4 streams: one row per stream in one
@@ -655,7 +659,7 @@ int vlac_sparse_prefill(vlac_ctx* ctx, const float* embeds, int B, int L_v, int 
     launch_resid_norm_rows(ctx->f16, ctx->h, m.max_seq, ctx->rpart, pending, rows_cap, ctx->h,
                            m.max_seq, ctx->rows + (size_t)(nl - 1) * ctx->max_rows, nullptr,
                            ctx->n_rows + (nl - 1), n_host, rows_cap, nullptr, m.rms_eps, m.d_model,
-                           ctx->xa, ctx->kpad_d / 16, st);
+                           ctx->xa, ctx->kpad_d / 16, st, &ctx->pending_adapt);
   if (out_attn_mean && attention_defers_stats(ctx, B, L_v, L_t))
     launch_stats_reduce(ctx, B, L_v, L_t, out_attn_mean, st);
   if (out_hidden)

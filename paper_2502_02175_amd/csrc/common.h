@@ -93,6 +93,13 @@ struct LayerW {
   float *s_qkv, *s_o, *s_gu, *s_down;  // e4m3 weights: scale per packed output row
 };
 
+// What launch_resid_norm_rows needs to know of the GEMM whose partial rows it adds up, where
+// that GEMM chooses its split factor on the device (tiles == 0: the factor is S as given)
+struct SplitAdapt {
+  const int* n_rows;  // device: the row count the GEMM ran with (n_rows_host >= 0: not read)
+  int n_rows_host, tiles, KS;
+};
+
 struct vlac_ctx {
   vlac_model_cfg cfg;
   bool f16;  // operands are fp16 (else bf16)
@@ -110,6 +117,7 @@ struct vlac_ctx {
   bf16_t *w_head, *embed;
   float* s_head;
   float* scale_tmp;  // scales in source row order while a matrix is being packed
+  SplitAdapt pending_adapt;  // of the FFN-down GEMM whose partial rows the next layer's first row kernel adds
   float* g_final;
   float *rope_cos, *rope_sin;  // [max_seq, hd/2]
   // workspace (device)
@@ -187,7 +195,7 @@ void launch_resid_norm_rows(bool f16, const float* resid, int resid_seq_stride, 
                             int S, int part_rows, float* h, int h_seq_stride, const int* rows,
                             const int* part_slot, const int* n_rows, int n_rows_host, int max_rows,
                             const float* gain, float eps, int d, bf16_t* xp, int KC,
-                            hipStream_t st);
+                            hipStream_t st, const SplitAdapt* adapt = nullptr);
 void launch_final_hidden(const float* src, int seq_stride, const int* rows, const int* n_rows,
                          int max_rows, const float* gain, float eps, int d, float* out, int L,
                          hipStream_t st);
@@ -240,6 +248,18 @@ struct NormIn {
   float* dst;          // where the completed rows are stored (never src), or null
   size_t dst_stride;
 };
+// The many-rows GEMM with a residual epilogue splits K where its work items (weight tiles x
+// row blocks of the ACTUAL row count) would leave half of the CUs idle and K is long enough
+// to carry the partial rows' cost: both that kernel and the row kernel that consumes the
+// partial rows compute the factor from the row count on the device with this function.
+// 1: not split, the GEMM adds to the residual stream itself.
+__host__ __device__ inline int tall_resid_splits(int items, int KS, int S_max) {
+  if (S_max <= 1 || KS < 64 || items > 128 || items < 1) return 1;
+  const int S = 256 / items;
+  return S > S_max ? S_max : S;
+}
+// the same for the GEMM that launch_gemm(EPI_RESID, ...) with these arguments launches
+SplitAdapt gemm_resid_adapt(vlac_ctx* c, int n_blocks, int kpad, int rows_cap, const int* n_rows, int n_rows_host);
 int gemm_init();  // one-time kernel attribute setup; returns hipError_t
 // returns the split-K factor used; for EPI_RESID a factor S > 1 means that the result is
 // NOT in the residual stream yet but in e.rpart as S partial rows (more than 32 rows:

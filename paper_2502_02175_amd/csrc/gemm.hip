@@ -582,6 +582,24 @@ bool gemm_can_fuse_norm(int n_rows_host, int decode_pos, int kpad) {
 // matrix-core bound and go to the kernel built for that.
 static const int kTallRows = 1024;
 
+// Most splits the many-rows GEMM with a residual epilogue may use (they need S partial rows
+// of fp32 per row in the workspace, and the row kernel that keeps a row in registers)
+static int tall_resid_smax(const vlac_ctx* c, int epi, int rows_cap, int d_model) {
+  if (epi != EPI_RESID || d_model > 8192) return 1;
+  return (size_t)3 * rows_cap * d_model <= c->rpart_floats ? 3 : 1;
+}
+
+SplitAdapt gemm_resid_adapt(vlac_ctx* c, int n_blocks, int kpad, int rows_cap, const int* n_rows, int n_rows_host) {
+  SplitAdapt ad = {nullptr, -1, 0, 0};
+  if (rows_cap >= kTallRows && tall_resid_smax(c, EPI_RESID, rows_cap, n_blocks * 32) > 1) {
+    ad.n_rows = n_rows;
+    ad.n_rows_host = n_rows_host;
+    ad.tiles = gemm_tall_tiles(n_blocks);
+    ad.KS = kpad / 64;
+  }
+  return ad;
+}
+
 int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, const float* wscale, int n_blocks, int kpad,
                 const bf16_t* xp,
                  const int* n_rows, int n_rows_host, int rows_cap, const GemmEpi& e, hipStream_t st,
@@ -633,7 +651,7 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, const float* wscale, int
       else launch_few<false, X_GLOBAL, false>(epi, a, a.P, 0, st);
     }
   } else if (rows_cap >= kTallRows) {
-    launch_gemm_tall(c->f16, epi, a, rows_cap, st);
+    launch_gemm_tall(c->f16, epi, a, rows_cap, tall_resid_smax(c, epi, rows_cap, e.d_model), st);
   } else {
     constexpr int MT = 4;
     const int tiles = (n_blocks + 3) / 4;

@@ -37,19 +37,23 @@ constexpr int NF = 2;       // feature blocks per wave
 constexpr int TALL_W = 8;   // waves per workgroup
 constexpr int XBUF = 3;     // LDS buffers of 4 row tiles x 4 k-tiles
 
+// (split s of S: this workgroup covers the 64-k steps [ks0, ks0 + KS) of the a.KS there are)
 template <int NA, int EPI, bool F16>
-__device__ __forceinline__ void tall_body(const GemmArgs& a, uint4* lds, int tile, int mb, int n_rows) {
+__device__ __forceinline__ void tall_body(const GemmArgs& a, uint4* lds, int tile, int mb, int n_rows,
+                                          int s, int S) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int row0 = mb * 128;
-  const int KC = 4 * a.KS, KS = a.KS;
+  const int KC = 4 * a.KS;
+  const int kq = a.KS / S, kr = a.KS % S;
+  const int ks0 = s * kq + min(s, kr), KS = kq + (s < kr ? 1 : 0);
   const int nb0 = tile * (TALL_W * NF) + w * NF;
   const uint4* wsrc[NF];
 #pragma unroll
   for (int fb = 0; fb < NF; ++fb)
-    wsrc[fb] = a.wp + (size_t)min(nb0 + fb, a.NB - 1) * KC * 64 + lane;
+    wsrc[fb] = a.wp + ((size_t)min(nb0 + fb, a.NB - 1) * KC + 4 * ks0) * 64 + lane;
   // this wave copies activation tiles j = 2 w, 2 w + 1 of a step's 16 (row tile j / 4, k-tile j % 4)
   const int mt0 = w >> 1, c0 = (w & 1) * 2;
-  const uint4* xsrc = a.xp + ((size_t)((row0 >> 5) + mt0) * KC + c0) * 64 + lane;
+  const uint4* xsrc = a.xp + ((size_t)((row0 >> 5) + mt0) * KC + 4 * ks0 + c0) * 64 + lane;
   uint4* xdst = lds + mt0 * 256 + c0 * 64;
 
   f32x16 acc[NF][NA];
@@ -139,6 +143,26 @@ __device__ __forceinline__ void tall_body(const GemmArgs& a, uint4* lds, int til
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no copy outlives the loop
 
   const int g = lane >> 5;
+  if (EPI == EPI_RESID && S > 1) {
+    // split K: the partial rows [split][row][feature] are left to the row kernel that follows
+    // (residual add + RMSNorm), which adds the splits up in order
+#pragma unroll
+    for (int mt = 0; mt < NA; ++mt) {
+      const int slot = row0 + mt * 32 + (lane & 31);
+      if (slot < n_rows) {
+#pragma unroll
+        for (int fb = 0; fb < NF; ++fb)
+          if (nb0 + fb < a.NB) {
+            float* dst = a.e.rpart + ((size_t)s * a.e.rpart_rows + slot) * a.e.d_model + (nb0 + fb) * 32 + 4 * g;
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+              *(float4*)(dst + 8 * q4) = make_float4(acc[fb][mt][4 * q4], acc[fb][mt][4 * q4 + 1],
+                                                     acc[fb][mt][4 * q4 + 2], acc[fb][mt][4 * q4 + 3]);
+          }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int mt = 0; mt < NA; ++mt) {
     const int slot = row0 + mt * 32 + (lane & 31);
@@ -154,22 +178,30 @@ __device__ __forceinline__ void tall_body(const GemmArgs& a, uint4* lds, int til
 template <int EPI, bool F16>
 __global__ __launch_bounds__(512) void gemm_tall_kernel(GemmArgs a) {
   __shared__ uint4 lds[XBUF * 4 * 256];  // 3 stages of 4 activation tiles x 4 k-tiles
-  // workgroup id -> (weight tile, row block); id % 8 is the XCD, and the row blocks of one
-  // weight tile follow each other on the same XCD.  (One workgroup per work item, sized
-  // for the largest possible row count: measured against a persistent grid that deals the
-  // items of the actual row count round-robin, the hardware's dynamic dispatch wins, and
-  // the workgroups that find no rows cost next to nothing.)
-  const int y = blockIdx.x >> 3;
-  const int mb = y % a.MB, tile = (y / a.MB) * 8 + (blockIdx.x & 7);
-  if (tile >= a.P) return;
+  // Work items are (weight tile, K split, row block) triples, listed with the row blocks of
+  // one tile and split next to each other, and the list is cut into eight equal runs, one
+  // per XCD (workgroup id % 8): an XCD's workgroups then share weight k-tiles through its
+  // L2 as they start in id order, and every XCD gets the same number of items whatever the
+  // tile count is.  The grid is sized for the largest possible row count and split factor;
+  // the items of the actual row count come first in every XCD's run, and a workgroup that
+  // finds none costs next to nothing (measured against a persistent grid that deals the
+  // items round-robin, the hardware's dynamic dispatch wins).
+  // (a.S > 1, residual epilogue only: how many K splits are used follows from the row
+  // count, see tall_resid_splits)
   const int n_rows = a.n_rows_val >= 0 ? a.n_rows_val : *a.n_rows;
+  const int MBn = (n_rows + 127) >> 7;
+  const int S = (EPI == EPI_RESID) ? tall_resid_splits(a.P * MBn, a.KS, a.S) : 1;
+  const int items = a.P * S * MBn, per = (items + 7) >> 3;
+  const int j = blockIdx.x >> 3, i = (blockIdx.x & 7) * per + j;
+  if (j >= per || i >= items) return;
+  const int vt = i / MBn, mb = i - vt * MBn;
+  const int tile = vt / S, s = vt - tile * S;
   const int row0 = mb * 128;
-  if (row0 >= n_rows) return;
   switch (min(4, (n_rows - row0 + 31) >> 5)) {
-    case 1: tall_body<1, EPI, F16>(a, lds, tile, mb, n_rows); break;
-    case 2: tall_body<2, EPI, F16>(a, lds, tile, mb, n_rows); break;
-    case 3: tall_body<3, EPI, F16>(a, lds, tile, mb, n_rows); break;
-    default: tall_body<4, EPI, F16>(a, lds, tile, mb, n_rows); break;
+    case 1: tall_body<1, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
+    case 2: tall_body<2, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
+    case 3: tall_body<3, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
+    default: tall_body<4, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
   }
 }
 
@@ -193,11 +225,13 @@ void launch_tall(int epi, const GemmArgs& a, int grid, hipStream_t st) {
 
 }  // namespace
 
-void launch_gemm_tall(bool f16, int epi, GemmArgs& a, int rows_cap, hipStream_t st) {
-  a.S = 1;
+int gemm_tall_tiles(int n_blocks) { return (n_blocks + TALL_W * NF - 1) / (TALL_W * NF); }
+
+void launch_gemm_tall(bool f16, int epi, GemmArgs& a, int rows_cap, int S_max, hipStream_t st) {
+  a.S = (epi == EPI_RESID && S_max > 1) ? S_max : 1;
   a.MB = (rows_cap + 127) / 128;
-  a.P = (a.NB + TALL_W * NF - 1) / (TALL_W * NF);  // weight tiles of 512 output features
-  const int grid = ((a.P + 7) / 8) * 8 * a.MB;
+  a.P = gemm_tall_tiles(a.NB);  // weight tiles of 512 output features
+  const int grid = ((a.P * a.S * a.MB + 7) / 8) * 8;
   if (f16) launch_tall<true>(epi, a, grid, st);
   else launch_tall<false>(epi, a, grid, st);
 }

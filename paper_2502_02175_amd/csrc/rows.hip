@@ -225,7 +225,7 @@ __global__ __launch_bounds__(256) void resid_norm_rows_kernel(
     const float* __restrict__ resid, int resid_seq_stride, const float* __restrict__ part, int S,
     int part_rows, float* __restrict__ h, int h_seq_stride, const int* __restrict__ rows,
     const int* __restrict__ part_slot, const int* __restrict__ n_rows, int n_rows_host,
-    const float* __restrict__ gain, float eps, int d, bf16_t* __restrict__ xp, int KC) {
+    const float* __restrict__ gain, float eps, int d, bf16_t* __restrict__ xp, int KC, SplitAdapt adapt) {
   __shared__ float red[4];
   const int slot = blockIdx.x, tid = threadIdx.x;
   if (slot >= (n_rows_host >= 0 ? n_rows_host : *n_rows)) return;
@@ -234,6 +234,16 @@ __global__ __launch_bounds__(256) void resid_norm_rows_kernel(
   const int pslot = part_slot ? part_slot[slot] : slot;
   const float* r = resid + ((size_t)(id >> 16) * resid_seq_stride + (id & 0xffff)) * d;
   float* y = h + ((size_t)(id >> 16) * h_seq_stride + (id & 0xffff)) * d;
+  if (adapt.tiles > 0) {
+    // the GEMM chose its split factor from its row count; unsplit, it added to the
+    // residual stream itself and left no partial rows
+    const int n_g = adapt.n_rows_host >= 0 ? adapt.n_rows_host : *adapt.n_rows;
+    S = tall_resid_splits(adapt.tiles * ((n_g + 127) >> 7), adapt.KS, S);
+    if (S == 1) {
+      S = 0;
+      r = y;
+    }
+  }
   const float* p0 = part + (size_t)pslot * d;
   const size_t pstride = (size_t)part_rows * d;
   const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -333,11 +343,13 @@ void launch_resid_norm_rows(bool f16, const float* resid, int resid_seq_stride, 
                             int S, int part_rows, float* h, int h_seq_stride, const int* rows,
                             const int* part_slot, const int* n_rows, int n_rows_host, int max_rows,
                             const float* gain, float eps, int d, bf16_t* xp, int KC,
-                            hipStream_t st) {
+                            hipStream_t st, const SplitAdapt* adapt) {
+  SplitAdapt ad = {nullptr, -1, 0, 0};
+  if (adapt) ad = *adapt;  // (never given for rows longer than 8192)
 #define VLAC_RN(K)                                                                               \
   hipLaunchKernelGGL(K, dim3(max_rows), dim3(256), 0, st, resid, resid_seq_stride, part, S,      \
                      part_rows, h, h_seq_stride, rows, part_slot, n_rows, n_rows_host, gain, eps, \
-                     d, xp, KC)
+                     d, xp, KC, ad)
   if (d <= 4096) {
     if (f16) VLAC_RN((resid_norm_rows_kernel<true, 4>));
     else VLAC_RN((resid_norm_rows_kernel<false, 4>));
@@ -345,6 +357,11 @@ void launch_resid_norm_rows(bool f16, const float* resid, int resid_seq_stride, 
     if (f16) VLAC_RN((resid_norm_rows_kernel<true, 8>));
     else VLAC_RN((resid_norm_rows_kernel<false, 8>));
   } else {
+#undef VLAC_RN
+#define VLAC_RN(K)                                                                               \
+  hipLaunchKernelGGL(K, dim3(max_rows), dim3(256), 0, st, resid, resid_seq_stride, part, S,      \
+                     part_rows, h, h_seq_stride, rows, part_slot, n_rows, n_rows_host, gain, eps, \
+                     d, xp, KC)
     if (f16) VLAC_RN(resid_norm_rows_long_kernel<true>);
     else VLAC_RN(resid_norm_rows_long_kernel<false>);
   }
