@@ -94,10 +94,10 @@ struct LayerW {
 };
 
 // What launch_resid_norm_rows needs to know of the GEMM whose partial rows it adds up, where
-// that GEMM chooses its split factor on the device (tiles == 0: the factor is S as given)
+// that GEMM chooses its split factor on the device (n_blocks == 0: the factor is S as given)
 struct SplitAdapt {
   const int* n_rows;  // device: the row count the GEMM ran with (n_rows_host >= 0: not read)
-  int n_rows_host, tiles, KS;
+  int n_rows_host, n_blocks, KS;  // the GEMM's feature blocks and 64-k steps
 };
 
 struct vlac_ctx {
@@ -248,15 +248,41 @@ struct NormIn {
   float* dst;          // where the completed rows are stored (never src), or null
   size_t dst_stride;
 };
-// The many-rows GEMM with a residual epilogue splits K where its work items (weight tiles x
-// row blocks of the ACTUAL row count) would leave half of the CUs idle and K is long enough
-// to carry the partial rows' cost: both that kernel and the row kernel that consumes the
-// partial rows compute the factor from the row count on the device with this function.
-// 1: not split, the GEMM adds to the residual stream itself.
-__host__ __device__ inline int tall_resid_splits(int items, int KS, int S_max) {
-  if (S_max <= 1 || KS < 64 || items > 128 || items < 1) return 1;
-  const int S = 256 / items;
-  return S > S_max ? S_max : S;
+// The many-rows GEMM decides on the device, from the ACTUAL row count, how it cuts its work
+// where weight tiles of 512 features x row blocks of 128 rows give less than one work item
+// per CU: weight tiles of 256 features (one feature block per wave instead of two), and,
+// with a residual epilogue, K split in up to S_max parts whose partial rows the row kernel
+// that follows adds up (S = 1: not split, the GEMM adds to the residual stream itself).
+// Both that kernel and the row kernel that consumes the partial rows call this function.
+struct TallPlan { int nf, tiles, S; };
+__host__ __device__ inline TallPlan tall_plan(int n_blocks, int row_blocks, int KS, int S_max) {
+  TallPlan best;
+  best.nf = 2;
+  best.tiles = (n_blocks + 15) >> 4;
+  best.S = 1;
+  const int items2 = best.tiles * row_blocks;
+  if (items2 > 256 || items2 < 1) return best;  // more than one round of work items as it is
+  // Less than one work item per CU: take the cut with the least estimated time,
+  // rounds of 256 items x the time of an item (in integers, so that host and device agree):
+  // an item of the narrow tile costs 0.575 of a wide one (half the MFMAs, 1.15 times the
+  // operand bytes per MFMA), a split divides K and adds 8 % per extra part for the partial rows.
+  if (S_max < 1 || KS < 64) S_max = 1;
+  if (S_max > 3) S_max = 3;
+  int best_cost = 0x7fffffff;
+  for (int nf = 2; nf >= 1; --nf) {
+    const int tiles = nf == 2 ? (n_blocks + 15) >> 4 : (n_blocks + 7) >> 3;
+    for (int S = 1; S <= S_max; ++S) {
+      const int items = tiles * S * row_blocks;
+      const int cost = ((items + 255) >> 8) * (nf == 2 ? 200 : 115) * (6 / S) * (100 + 8 * (S - 1));
+      if (cost < best_cost) {
+        best_cost = cost;
+        best.nf = nf;
+        best.tiles = tiles;
+        best.S = S;
+      }
+    }
+  }
+  return best;
 }
 // the same for the GEMM that launch_gemm(EPI_RESID, ...) with these arguments launches
 SplitAdapt gemm_resid_adapt(vlac_ctx* c, int n_blocks, int kpad, int rows_cap, const int* n_rows, int n_rows_host);

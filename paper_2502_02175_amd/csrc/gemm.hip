@@ -578,9 +578,16 @@ bool gemm_can_fuse_norm(int n_rows_host, int decode_pos, int kpad) {
          (size_t)(kpad / 8) * n_rows_host * 16 <= kStageBytes;
 }
 
-// From this many rows on (the capacity of the launch: streams x tokens) the GEMMs are
-// matrix-core bound and go to the kernel built for that.
-static const int kTallRows = 1024;
+// From this many rows on (the capacity of the launch: streams x tokens; the actual row count
+// is known on the device only) the GEMMs go to the kernel built for matrix-core bound
+// work.  Measured at the 7B shape, 32 layers, by ACTUAL row count: the one-stream kernel
+// wins below about 250 rows (218 rows: 7.1 against 7.8 ms per prefill), the many-rows
+// kernel above (327 rows: 10.3 against 9.2 ms, 576 rows: 13.8 against 10.2 ms); a
+// capacity of 512 rows (two 7B streams, one stream with two camera views) mostly means
+// more than 250 recomputed rows.  (Weights stored as e4m3 codes: the many-rows kernel has
+// no variant for them, and 1024 rows or more are refused at the entry point.)
+static const int kTallRows = 512;
+static bool use_tall(const vlac_ctx* c, int rows_cap) { return rows_cap >= kTallRows && !c->w8; }
 
 // Most splits the many-rows GEMM with a residual epilogue may use (they need S partial rows
 // of fp32 per row in the workspace, and the row kernel that keeps a row in registers)
@@ -591,10 +598,10 @@ static int tall_resid_smax(const vlac_ctx* c, int epi, int rows_cap, int d_model
 
 SplitAdapt gemm_resid_adapt(vlac_ctx* c, int n_blocks, int kpad, int rows_cap, const int* n_rows, int n_rows_host) {
   SplitAdapt ad = {nullptr, -1, 0, 0};
-  if (rows_cap >= kTallRows && tall_resid_smax(c, EPI_RESID, rows_cap, n_blocks * 32) > 1) {
+  if (use_tall(c, rows_cap) && tall_resid_smax(c, EPI_RESID, rows_cap, n_blocks * 32) > 1) {
     ad.n_rows = n_rows;
     ad.n_rows_host = n_rows_host;
-    ad.tiles = gemm_tall_tiles(n_blocks);
+    ad.n_blocks = n_blocks;
     ad.KS = kpad / 64;
   }
   return ad;
@@ -650,7 +657,7 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, const float* wscale, int
       else if (c->f16) launch_few<true, X_GLOBAL, false>(epi, a, a.P, 0, st);
       else launch_few<false, X_GLOBAL, false>(epi, a, a.P, 0, st);
     }
-  } else if (rows_cap >= kTallRows) {
+  } else if (use_tall(c, rows_cap)) {
     launch_gemm_tall(c->f16, epi, a, rows_cap, tall_resid_smax(c, epi, rows_cap, e.d_model), st);
   } else {
     constexpr int MT = 4;

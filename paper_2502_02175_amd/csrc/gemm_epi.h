@@ -134,4 +134,3 @@ __device__ inline void epilogue_tile(const GemmEpi& e, int nb, int slot, int id,
 // gemm_tall.hip: the kernel for many rows (matrix-core bound).  The caller has filled
 // every field of `a` except S, MB and P.
 void launch_gemm_tall(bool f16, int epi, GemmArgs& a, int rows_cap, int S_max, hipStream_t st);
-int gemm_tall_tiles(int n_blocks);

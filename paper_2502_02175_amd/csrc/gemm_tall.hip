@@ -19,7 +19,10 @@
 //    copied global -> LDS directly (global_load_lds_dwordx4: lane l's 16 bytes land at
 //    base + 16 l, which is the fragment order itself), two steps ahead, into a ring of 3
 //    buffers: no staging registers, no LDS store instructions, one barrier per step.
-//  * No split of K: tiles x row blocks fill the chip by themselves.
+//  * K is split only where tiles x row blocks leave half the chip idle, and only in the
+//    residual GEMMs (O, FFN-down), whose consumer (residual add + RMSNorm) can add the
+//    partial rows up: the split factor follows from the row count on the device
+//    (tall_resid_splits).  Everywhere else tiles x row blocks fill the chip by themselves.
 //  * Tried and measured, not kept: 4 waves x 4 feature blocks (one wave per SIMD: 12%
 //    slower), staging the activation tiles through registers (the extra registers and
 //    LDS stores cost 3%), a 256 x 256 tile whose weight tiles are fetched by two waves
@@ -33,12 +36,12 @@
 
 namespace {
 
-constexpr int NF = 2;       // feature blocks per wave
 constexpr int TALL_W = 8;   // waves per workgroup
 constexpr int XBUF = 3;     // LDS buffers of 4 row tiles x 4 k-tiles
 
 // (split s of S: this workgroup covers the 64-k steps [ks0, ks0 + KS) of the a.KS there are)
-template <int NA, int EPI, bool F16>
+// NF: feature blocks per wave (2: the workgroup tile is 512 features wide, 1: 256)
+template <int NF, int NA, int EPI, bool F16>
 __device__ __forceinline__ void tall_body(const GemmArgs& a, uint4* lds, int tile, int mb, int n_rows,
                                           int s, int S) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -106,16 +109,18 @@ __device__ __forceinline__ void tall_body(const GemmArgs& a, uint4* lds, int til
   };
   // Step i at phase ph = i % 3 of the unrolled loop: its k-tiles sit in slots
   // (4 ph + c) % 6 and its activation tiles in LDS buffer ph.  They were asked for at the
-  // start of step i - 2; behind them this wave has issued 2 x 8 weight loads and the two
-  // copies of step i + 1, so "at most 18 loads outstanding" means they have landed; the
+  // start of step i - 2; behind them this wave has issued 2 x 4 NF weight loads and the two
+  // copies of step i + 1, so "at most 8 NF + 2 loads outstanding" means they have landed; the
   // barrier then makes that true for the copies of all 8 waves, and says that every wave
   // is done with step i - 1, whose buffer takes the tiles of step i + 2.
   // (In the one or two steps after the last full turn of the loop the count does not hold:
   // the weight loads of those steps refill slots that nobody reads any more, and the
   // compiler drops them.  There the wait is for everything.)
-#define VLAC_TALL_STEP(i, ph, s0, s1, s2, s3, WAIT)          \
+#define VLAC_TALL_STEP(i, ph, s0, s1, s2, s3, ALL)           \
   {                                                          \
-    asm volatile(WAIT ::: "memory");                         \
+    if (ALL) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                  \
+    else if (NF == 2) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");        \
+    else asm volatile("s_waitcnt vmcnt(10)" ::: "memory");                     \
     __syncthreads();                                         \
     copy_x((i) + 2, ((ph) + 2) % 3);                         \
     ktile((i), 0, ph, W[s0]);                                \
@@ -128,16 +133,18 @@ __device__ __forceinline__ void tall_body(const GemmArgs& a, uint4* lds, int til
   copy_x(1, 1);
 #pragma unroll
   for (int kt = 0; kt < 6; ++kt) load_w(kt, W[kt]);
-  asm volatile("s_waitcnt vmcnt(12)" ::: "memory");  // both copies; the 12 weight loads fly on
+  // both copies; the 6 NF weight loads fly on
+  if (NF == 2) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
   int i = 0;
   for (; i + 3 <= KS; i += 3) {
-    VLAC_TALL_STEP(i, 0, 0, 1, 2, 3, "s_waitcnt vmcnt(18)")
-    VLAC_TALL_STEP(i + 1, 1, 4, 5, 0, 1, "s_waitcnt vmcnt(18)")
-    VLAC_TALL_STEP(i + 2, 2, 2, 3, 4, 5, "s_waitcnt vmcnt(18)")
+    VLAC_TALL_STEP(i, 0, 0, 1, 2, 3, false)
+    VLAC_TALL_STEP(i + 1, 1, 4, 5, 0, 1, false)
+    VLAC_TALL_STEP(i + 2, 2, 2, 3, 4, 5, false)
   }
   if (i < KS) {
-    VLAC_TALL_STEP(i, 0, 0, 1, 2, 3, "s_waitcnt vmcnt(0)")
-    if (i + 1 < KS) VLAC_TALL_STEP(i + 1, 1, 4, 5, 0, 1, "s_waitcnt vmcnt(0)")
+    VLAC_TALL_STEP(i, 0, 0, 1, 2, 3, true)
+    if (i + 1 < KS) VLAC_TALL_STEP(i + 1, 1, 4, 5, 0, 1, true)
   }
 #undef VLAC_TALL_STEP
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no copy outlives the loop
@@ -190,18 +197,29 @@ __global__ __launch_bounds__(512) void gemm_tall_kernel(GemmArgs a) {
   // count, see tall_resid_splits)
   const int n_rows = a.n_rows_val >= 0 ? a.n_rows_val : *a.n_rows;
   const int MBn = (n_rows + 127) >> 7;
-  const int S = (EPI == EPI_RESID) ? tall_resid_splits(a.P * MBn, a.KS, a.S) : 1;
-  const int items = a.P * S * MBn, per = (items + 7) >> 3;
+  const TallPlan pl = tall_plan(a.NB, MBn, a.KS, EPI == EPI_RESID ? a.S : 1);
+  const int S = pl.S;
+  const int items = pl.tiles * S * MBn, per = (items + 7) >> 3;
   const int j = blockIdx.x >> 3, i = (blockIdx.x & 7) * per + j;
   if (j >= per || i >= items) return;
   const int vt = i / MBn, mb = i - vt * MBn;
   const int tile = vt / S, s = vt - tile * S;
   const int row0 = mb * 128;
-  switch (min(4, (n_rows - row0 + 31) >> 5)) {
-    case 1: tall_body<1, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
-    case 2: tall_body<2, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
-    case 3: tall_body<3, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
-    default: tall_body<4, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
+  const int na = min(4, (n_rows - row0 + 31) >> 5);
+  if (pl.nf == 2) {
+    switch (na) {
+      case 1: tall_body<2, 1, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
+      case 2: tall_body<2, 2, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
+      case 3: tall_body<2, 3, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
+      default: tall_body<2, 4, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
+    }
+  } else {
+    switch (na) {
+      case 1: tall_body<1, 1, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
+      case 2: tall_body<1, 2, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
+      case 3: tall_body<1, 3, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
+      default: tall_body<1, 4, EPI, F16>(a, lds, tile, mb, n_rows, s, S); break;
+    }
   }
 }
 
@@ -225,13 +243,18 @@ void launch_tall(int epi, const GemmArgs& a, int grid, hipStream_t st) {
 
 }  // namespace
 
-int gemm_tall_tiles(int n_blocks) { return (n_blocks + TALL_W * NF - 1) / (TALL_W * NF); }
-
 void launch_gemm_tall(bool f16, int epi, GemmArgs& a, int rows_cap, int S_max, hipStream_t st) {
   a.S = (epi == EPI_RESID && S_max > 1) ? S_max : 1;
   a.MB = (rows_cap + 127) / 128;
-  a.P = gemm_tall_tiles(a.NB);  // weight tiles of 512 output features
-  const int grid = ((a.P * a.S * a.MB + 7) / 8) * 8;
+  a.P = 0;
+  // the grid covers the most work items any row count up to rows_cap can give: of both tile
+  // widths and every split factor the plan can choose
+  int most = 0;
+  for (int mb = 1; mb <= a.MB; ++mb) {
+    const TallPlan pl = tall_plan(a.NB, mb, a.KS, a.S);
+    most = std::max(most, pl.tiles * pl.S * mb);
+  }
+  const int grid = ((most + 7) / 8) * 8;
   if (f16) launch_tall<true>(epi, a, grid, st);
   else launch_tall<false>(epi, a, grid, st);
 }

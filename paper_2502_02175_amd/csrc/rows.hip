@@ -234,11 +234,11 @@ __global__ __launch_bounds__(256) void resid_norm_rows_kernel(
   const int pslot = part_slot ? part_slot[slot] : slot;
   const float* r = resid + ((size_t)(id >> 16) * resid_seq_stride + (id & 0xffff)) * d;
   float* y = h + ((size_t)(id >> 16) * h_seq_stride + (id & 0xffff)) * d;
-  if (adapt.tiles > 0) {
+  if (adapt.n_blocks > 0) {
     // the GEMM chose its split factor from its row count; unsplit, it added to the
     // residual stream itself and left no partial rows
     const int n_g = adapt.n_rows_host >= 0 ? adapt.n_rows_host : *adapt.n_rows;
-    S = tall_resid_splits(adapt.tiles * ((n_g + 127) >> 7), adapt.KS, S);
+    S = tall_plan(adapt.n_blocks, (n_g + 127) >> 7, adapt.KS, S).S;
     if (S == 1) {
       S = 0;
       r = y;
