@@ -261,9 +261,9 @@ __host__ __device__ inline TallPlan tall_plan(int n_blocks, int row_blocks, int 
   best.tiles = (n_blocks + 15) >> 4;
   best.S = 1;
   const int items2 = best.tiles * row_blocks;
-  if (items2 > 256 || items2 < 1) return best;  // more than one round of work items as it is
-  // Less than one work item per CU: take the cut with the least estimated time,
-  // rounds of 256 items x the time of an item (in integers, so that host and device agree):
+  if (items2 > 128 || items2 < 1) return best;  // no other cut fits into one round of 256 items
+  // Less than one work item per two CUs: of the cuts that still give at most 256 items, take
+  // the one with the least estimated item time (in integers, so that host and device agree):
   // an item of the narrow tile costs 0.575 of a wide one (half the MFMAs, 1.15 times the
   // operand bytes per MFMA), a split divides K and adds 8 % per extra part for the partial rows.
   if (S_max < 1 || KS < 64) S_max = 1;
@@ -272,8 +272,8 @@ __host__ __device__ inline TallPlan tall_plan(int n_blocks, int row_blocks, int 
   for (int nf = 2; nf >= 1; --nf) {
     const int tiles = nf == 2 ? (n_blocks + 15) >> 4 : (n_blocks + 7) >> 3;
     for (int S = 1; S <= S_max; ++S) {
-      const int items = tiles * S * row_blocks;
-      const int cost = ((items + 255) >> 8) * (nf == 2 ? 200 : 115) * (6 / S) * (100 + 8 * (S - 1));
+      if (tiles * S * row_blocks > 256) continue;
+      const int cost = (nf == 2 ? 200 : 115) * (6 / S) * (100 + 8 * (S - 1));
       if (cost < best_cost) {
         best_cost = cost;
         best.nf = nf;
