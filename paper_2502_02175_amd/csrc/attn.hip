@@ -281,9 +281,13 @@ __global__ __launch_bounds__(256, 3) void attn_rows4_kernel(AttnArgs a) {
   const int b = blockIdx.z, h = blockIdx.y;
   const int off_b = a.slot_off[b];
   const int n_b = a.slot_off[b + 1] - off_b;
-  if ((int)blockIdx.x * 128 >= n_b || n_b < a.rows4_from) return;
-  const int qt = blockIdx.x * 4 + w, s0 = qt * 32;  // this wave's query tile
-  const bool active = s0 < n_b;
+  // the stream's query tiles are dealt to its workgroups in equal shares of at most 4 (33
+  // tiles: 9 workgroups of 3 or 4, not 8 of 4 and one with a single busy wave)
+  const int n_qt = (n_b + 31) >> 5, n_wg = (n_qt + 3) >> 2;
+  if ((int)blockIdx.x >= n_wg || n_b < a.rows4_from) return;
+  const int qt_end = ((int)blockIdx.x + 1) * n_qt / n_wg;
+  const int qt = (int)blockIdx.x * n_qt / n_wg + w, s0 = qt * 32;  // this wave's query tile
+  const bool active = qt < qt_end;
   const int hk = h / (a.n_q_heads / a.n_kv_heads);
   const bool valid = active && s0 + j < n_b;
   const int sg = off_b + (valid ? s0 + j : n_b - 1);  // this lane's query slot
@@ -292,7 +296,7 @@ __global__ __launch_bounds__(256, 3) void attn_rows4_kernel(AttnArgs a) {
   const int n_kt = (pos_last >> 5) + 1;  // 0 for a wave without queries
   const int pos_first = __builtin_amdgcn_readfirstlane(pos);  // lane 0: the wave's first query
   // rows ascend by position: the workgroup needs the key tiles of its last query
-  const int pos_wg = a.rows[off_b + min((int)blockIdx.x * 128 + 127, n_b - 1)] & 0xffff;
+  const int pos_wg = a.rows[off_b + min(qt_end * 32 - 1, n_b - 1)] & 0xffff;
   const int n_kt_wg = (pos_wg >> 5) + 1;
 
   const size_t head_elems = (size_t)a.max_seq * HD;
