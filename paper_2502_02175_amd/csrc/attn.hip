@@ -256,6 +256,20 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a) {
   }
 }
 
+// Two probabilities -> one operand dword.  They lie in [0, 256], so the fp16 conversion
+// (round to nearest even, as everywhere) needs no saturation.
+template <bool F16>
+__device__ inline uint32_t pack_p2(float lo, float hi) {
+  if constexpr (F16) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+  } else {
+    return pack_op2<false>(lo, hi);
+  }
+}
+
 // ---------------------------------------------------------------------------
 // The same attention for MANY query tiles per stream (long sequences, many streams): one
 // query tile per WAVE.  The 4 waves of a workgroup walk the key tiles together and share
@@ -427,10 +441,10 @@ __global__ __launch_bounds__(256, 3) void attn_rows4_kernel(AttnArgs a) {
       uint4 pb[2];
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        pb[t].x = pack_op2<F16>(pr[8 * t + 0], pr[8 * t + 1]);
-        pb[t].y = pack_op2<F16>(pr[8 * t + 2], pr[8 * t + 3]);
-        pb[t].z = pack_op2<F16>(pr[8 * t + 4], pr[8 * t + 5]);
-        pb[t].w = pack_op2<F16>(pr[8 * t + 6], pr[8 * t + 7]);
+        pb[t].x = pack_p2<F16>(pr[8 * t + 0], pr[8 * t + 1]);
+        pb[t].y = pack_p2<F16>(pr[8 * t + 2], pr[8 * t + 3]);
+        pb[t].z = pack_p2<F16>(pr[8 * t + 4], pr[8 * t + 5]);
+        pb[t].w = pack_p2<F16>(pr[8 * t + 6], pr[8 * t + 7]);
       }
       if (rescale) {
 #pragma unroll
