@@ -203,15 +203,68 @@ __global__ __launch_bounds__(256) void rmsnorm_rows_kernel(
   }
 }
 
+// The same for rows of at most 512 NI elements: a lane keeps its share of the row (and of the
+// gains) in registers, so every load of a row is in flight at once and the row is read once;
+// with few rows (a decode pass over some streams) the kernel is all latency.
+template <bool F16, int NI>
+__global__ __launch_bounds__(256) void rmsnorm_rows_reg_kernel(
+    const float* __restrict__ src, int seq_stride, const int* __restrict__ rows,
+    const int* __restrict__ n_rows, int n_rows_host, int decode_pos,
+    const float* __restrict__ gain, float eps, int d, bf16_t* __restrict__ xp, int KC) {
+  const int slot = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (slot >= (n_rows_host >= 0 ? n_rows_host : *n_rows)) return;
+  const int id = decode_pos >= 0 ? ((slot << 16) | decode_pos) : rows[slot];
+  const float* x = src + ((size_t)(id >> 16) * seq_stride + (id & 0xffff)) * d;
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 a[NI], b[NI], ga[NI], gb[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int k = lane * 8 + i * 512;
+    a[i] = b[i] = ga[i] = gb[i] = zero;
+    if (k < d) {
+      a[i] = *(const float4*)(x + k);
+      b[i] = *(const float4*)(x + k + 4);
+      ga[i] = *(const float4*)(gain + k);
+      gb[i] = *(const float4*)(gain + k + 4);
+    }
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+    ss += a[i].x * a[i].x + a[i].y * a[i].y + a[i].z * a[i].z + a[i].w * a[i].w +
+          (b[i].x * b[i].x + b[i].y * b[i].y + b[i].z * b[i].z + b[i].w * b[i].w);
+  ss = wave_sum(ss);
+  const float r = rsqrtf(ss / (float)d + eps);
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int k = lane * 8 + i * 512;
+    if (k < d) {
+      uint4 o;
+      o.x = pack_op2<F16>(a[i].x * r * ga[i].x, a[i].y * r * ga[i].y);
+      o.y = pack_op2<F16>(a[i].z * r * ga[i].z, a[i].w * r * ga[i].w);
+      o.z = pack_op2<F16>(b[i].x * r * gb[i].x, b[i].y * r * gb[i].y);
+      o.w = pack_op2<F16>(b[i].z * r * gb[i].z, b[i].w * r * gb[i].w);
+      *(uint4*)(xp + frag_off(slot, k, KC)) = o;
+    }
+  }
+}
+
 void launch_rmsnorm_rows(bool f16, const float* src, int seq_stride, const int* rows,
                          const int* n_rows, int n_rows_host, int decode_pos, int max_rows,
                          const float* gain, float eps, int d, bf16_t* xp, int KC, hipStream_t st) {
-  if (f16)
-    hipLaunchKernelGGL(rmsnorm_rows_kernel<true>, dim3((max_rows + 3) / 4), dim3(256), 0, st, src,
-                       seq_stride, rows, n_rows, n_rows_host, decode_pos, gain, eps, d, xp, KC);
-  else
-    hipLaunchKernelGGL(rmsnorm_rows_kernel<false>, dim3((max_rows + 3) / 4), dim3(256), 0, st, src,
-                       seq_stride, rows, n_rows, n_rows_host, decode_pos, gain, eps, d, xp, KC);
+  const dim3 grid((max_rows + 3) / 4), block(256);
+#define VLAC_NORM_ARGS src, seq_stride, rows, n_rows, n_rows_host, decode_pos, gain, eps, d, xp, KC
+  if (d <= 2048) {
+    if (f16) hipLaunchKernelGGL((rmsnorm_rows_reg_kernel<true, 4>), grid, block, 0, st, VLAC_NORM_ARGS);
+    else hipLaunchKernelGGL((rmsnorm_rows_reg_kernel<false, 4>), grid, block, 0, st, VLAC_NORM_ARGS);
+  } else if (d <= 4096) {
+    if (f16) hipLaunchKernelGGL((rmsnorm_rows_reg_kernel<true, 8>), grid, block, 0, st, VLAC_NORM_ARGS);
+    else hipLaunchKernelGGL((rmsnorm_rows_reg_kernel<false, 8>), grid, block, 0, st, VLAC_NORM_ARGS);
+  } else {
+    if (f16) hipLaunchKernelGGL(rmsnorm_rows_kernel<true>, grid, block, 0, st, VLAC_NORM_ARGS);
+    else hipLaunchKernelGGL(rmsnorm_rows_kernel<false>, grid, block, 0, st, VLAC_NORM_ARGS);
+  }
+#undef VLAC_NORM_ARGS
 }
 
 // Residual add with the split-K partial rows of the projection that came before, then
