@@ -273,7 +273,7 @@ void launch_rmsnorm_rows(bool f16, const float* src, int seq_stride, const int* 
 // stays in registers (MAXI float4 per thread, d <= 1024 * MAXI), and all of a thread's
 // loads of the row and of two splits are in flight together: the work per row is all
 // latency.  gain == nullptr: no norm.
-template <bool F16, int MAXI>
+template <bool F16, int MAXI, int NS>
 __global__ __launch_bounds__(256) void resid_norm_rows_kernel(
     const float* __restrict__ resid, int resid_seq_stride, const float* __restrict__ part, int S,
     int part_rows, float* __restrict__ h, int h_seq_stride, const int* __restrict__ rows,
@@ -300,9 +300,10 @@ __global__ __launch_bounds__(256) void resid_norm_rows_kernel(
   const float* p0 = part + (size_t)pslot * d;
   const size_t pstride = (size_t)part_rows * d;
   const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-  // NS splits are in flight at a time (all 8 for rows of up to 4096 elements): a split past
-  // the last one is loaded from the last (a valid address, no branch) and not added
-  constexpr int NS = MAXI <= 4 ? 8 : 4;
+  // NS splits are in flight at a time (all 8 for rows of up to 4096 elements where the GEMM
+  // may have split that far; 4 where it splits less, which leaves registers for more rows
+  // per CU): a split past the last one is loaded from the last (a valid address, no branch)
+  // and not added
   float4 v[MAXI], g[MAXI], t[NS][MAXI];
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) {
@@ -335,7 +336,7 @@ __global__ __launch_bounds__(256) void resid_norm_rows_kernel(
 #pragma unroll
   for (int i = 0; i < MAXI; ++i) {
     const int k = tid * 4 + i * 1024;
-    if (k < d) *(float4*)(y + k) = v[i];
+    if (k < d && (S > 0 || r != y)) *(float4*)(y + k) = v[i];  // (unsplit in place: h holds it already)
     ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
   }
   if (!gain) return;
@@ -403,12 +404,15 @@ void launch_resid_norm_rows(bool f16, const float* resid, int resid_seq_stride, 
   hipLaunchKernelGGL(K, dim3(max_rows), dim3(256), 0, st, resid, resid_seq_stride, part, S,      \
                      part_rows, h, h_seq_stride, rows, part_slot, n_rows, n_rows_host, gain, eps, \
                      d, xp, KC, ad)
-  if (d <= 4096) {
-    if (f16) VLAC_RN((resid_norm_rows_kernel<true, 4>));
-    else VLAC_RN((resid_norm_rows_kernel<false, 4>));
+  if (d <= 4096 && S <= 4) {
+    if (f16) VLAC_RN((resid_norm_rows_kernel<true, 4, 4>));
+    else VLAC_RN((resid_norm_rows_kernel<false, 4, 4>));
+  } else if (d <= 4096) {
+    if (f16) VLAC_RN((resid_norm_rows_kernel<true, 4, 8>));
+    else VLAC_RN((resid_norm_rows_kernel<false, 4, 8>));
   } else if (d <= 8192) {
-    if (f16) VLAC_RN((resid_norm_rows_kernel<true, 8>));
-    else VLAC_RN((resid_norm_rows_kernel<false, 8>));
+    if (f16) VLAC_RN((resid_norm_rows_kernel<true, 8, 4>));
+    else VLAC_RN((resid_norm_rows_kernel<false, 8, 4>));
   } else {
 #undef VLAC_RN
 #define VLAC_RN(K)                                                                               \
