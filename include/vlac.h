@@ -70,8 +70,9 @@ enum { VLAC_OPERAND_BF16 = 0, VLAC_OPERAND_F16 = 1, VLAC_OPERAND_F16_W8 = 2 };
  * output feature (the smallest with max|w_row| / scale <= 448; codes by round to nearest,
  * ties to even; see vlac_quantize_e4m3), and the kernels expand the codes to fp16 in
  * registers, which is exact.  The weights handed over are bf16 as always; the result is
- * that of the F16 mode with the quantised weights.  Serves up to 1023 rows per launch
- * (one stream, small batches): larger prefills return VLAC_E_STATE. */
+ * that of the F16 mode with the quantised weights.  Launches of 1024 rows or more (batched
+ * streams), which are bound by the matrix cores and not by the weights, expand each matrix
+ * to fp16 in a workspace of the context before they use it. */
 
 /* One decoder layer, device pointers, bf16, row-major [out_features, in_features]
  * (y = x W^T).  wqkv rows: all query heads, then all key heads, then all value

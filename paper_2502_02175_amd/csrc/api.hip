@@ -60,7 +60,7 @@ void free_all(vlac_ctx* c) {
     }
     free(c->layers);
   }
-  void* dev[] = {c->w_head, c->s_head, c->scale_tmp, c->embed, c->g_final, c->rope_cos, c->rope_sin, c->h, c->hdec, c->xa, c->xf,
+  void* dev[] = {c->w_head, c->s_head, c->scale_tmp, c->wdeq, c->embed, c->g_final, c->rope_cos, c->rope_sin, c->h, c->hdec, c->xa, c->xf,
                  c->qbuf, c->partial, c->rpart, c->counters, c->rows, c->prev_slot, c->n_rows, c->slot_off, c->rank,
                  c->m_layer, c->n_rows_bl, c->statp, c->stat_counters, c->logits, c->tokens,
                  c->dec_rows, c->terms, c->flags, c->embed_list, c->embed_n, c->relevance, c->errword, c->scratch_i,
@@ -159,6 +159,15 @@ int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out) {
   A_(w_head, frag_elems(m.vocab, ctx->kpad_d) / wdiv);
   if (ctx->w8) A_(s_head, m.vocab);
   if (ctx->w8) A_(scale_tmp, max_out);
+  if (ctx->w8 && mr >= 1024) {
+    // the many-rows GEMM has no variant for e4m3 codes: a launch of 1024 rows or more expands
+    // its matrix to fp16 first (the largest of a layer's four fits here)
+    size_t most = frag_elems(ctx->qkv_dim, ctx->kpad_d);
+    most = std::max(most, frag_elems(m.d_model, ctx->kpad_q));
+    most = std::max(most, frag_elems(2 * m.d_ffn, ctx->kpad_d));
+    most = std::max(most, frag_elems(m.d_model, ctx->kpad_f));
+    A_(wdeq, most);
+  }
   A_(embed, (size_t)m.vocab * m.d_model);
   A_(g_final, m.d_model);
   A_(rope_cos, (size_t)ms * (m.head_dim / 2));
@@ -645,7 +654,6 @@ int vlac_sparse_prefill(vlac_ctx* ctx, const float* embeds, int B, int L_v, int 
   const int nl = m.n_layers;
   launch_plan(ctx, B, L_v, L_t, reuse_order, reuse_count, stride, layer_count, st);
   const int rows_cap = B * L;
-  if (ctx->w8 && rows_cap >= 1024) return VLAC_E_STATE;  // e4m3 weights: no many-rows kernel
   const int n_host = reuse_order ? -1 : rows_cap;
   int pending = 0;
   for (int l = 0; l < nl; ++l) {

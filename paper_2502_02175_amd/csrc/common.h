@@ -117,6 +117,7 @@ struct vlac_ctx {
   bf16_t *w_head, *embed;
   float* s_head;
   float* scale_tmp;  // scales in source row order while a matrix is being packed
+  bf16_t* wdeq;      // e4m3 weights, many rows: one matrix expanded to fp16 for the many-rows GEMM
   SplitAdapt pending_adapt;  // of the FFN-down GEMM whose partial rows the next layer's first row kernel adds
   float* g_final;
   float *rope_cos, *rope_sin;  // [max_seq, hd/2]

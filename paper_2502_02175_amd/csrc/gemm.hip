@@ -585,9 +585,13 @@ bool gemm_can_fuse_norm(int n_rows_host, int decode_pos, int kpad) {
 // kernel above (327 rows: 10.3 against 9.2 ms, 576 rows: 13.8 against 10.2 ms); a
 // capacity of 512 rows (two 7B streams, one stream with two camera views) mostly means
 // more than 250 recomputed rows.  (Weights stored as e4m3 codes: the many-rows kernel has
-// no variant for them, and 1024 rows or more are refused at the entry point.)
+// no variant for them; up to 1023 rows stay with the one-stream kernel, from 1024 rows on
+// the matrix is expanded to fp16 before every launch, 3 bytes of traffic per weight
+// against the 2 rows flops per weight that such a launch spends on it.)
 static const int kTallRows = 512;
-static bool use_tall(const vlac_ctx* c, int rows_cap) { return rows_cap >= kTallRows && !c->w8; }
+static bool use_tall(const vlac_ctx* c, int rows_cap) {
+  return rows_cap >= kTallRows && (!c->w8 || (rows_cap >= 1024 && c->wdeq));
+}
 
 // Most splits the many-rows GEMM with a residual epilogue may use (they need S partial rows
 // of fp32 per row in the workspace, and the row kernel that keeps a row in registers)
@@ -658,6 +662,10 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, const float* wscale, int
       else launch_few<false, X_GLOBAL, false>(epi, a, a.P, 0, st);
     }
   } else if (use_tall(c, rows_cap)) {
+    if (c->w8) {
+      launch_expand_e4m3(a.wp, (uint4*)c->wdeq, (size_t)n_blocks * 2 * a.KS, st);
+      a.wp = (const uint4*)c->wdeq;
+    }
     launch_gemm_tall(c->f16, epi, a, rows_cap, tall_resid_smax(c, epi, rows_cap, e.d_model), st);
   } else {
     constexpr int MT = 4;

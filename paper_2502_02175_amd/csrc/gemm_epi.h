@@ -134,3 +134,5 @@ __device__ inline void epilogue_tile(const GemmEpi& e, int nb, int slot, int id,
 // gemm_tall.hip: the kernel for many rows (matrix-core bound).  The caller has filled
 // every field of `a` except S, MB and P.
 void launch_gemm_tall(bool f16, int epi, GemmArgs& a, int rows_cap, int S_max, hipStream_t st);
+// e4m3 weight codes (n_slots slots of two k-tiles, 64 uint4 each) -> fp16 tiles, fragment order
+void launch_expand_e4m3(const uint4* codes, uint4* tiles, size_t n_slots, hipStream_t st);

@@ -150,6 +150,14 @@ __device__ __forceinline__ void tall_body(const GemmArgs& a, uint4* lds, int til
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no copy outlives the loop
 
   const int g = lane >> 5;
+  if (a.wscale) {  // weights expanded from e4m3 codes: the scale of every output feature
+#pragma unroll
+    for (int fb = 0; fb < NF; ++fb)
+      if (nb0 + fb < a.NB) {
+#pragma unroll
+        for (int mt = 0; mt < NA; ++mt) scale_tile(a.wscale, nb0 + fb, g, acc[fb][mt]);
+      }
+  }
   if (EPI == EPI_RESID && S > 1) {
     // split K: the partial rows [split][row][feature] are left to the row kernel that follows
     // (residual add + RMSNorm), which adds the splits up in order
@@ -241,7 +249,23 @@ void launch_tall(int epi, const GemmArgs& a, int grid, hipStream_t st) {
   }
 }
 
+__global__ __launch_bounds__(256) void expand_e4m3_kernel(const uint4* __restrict__ codes,
+                                                          uint4* __restrict__ tiles, size_t n) {
+  // thread = one lane's slot: the 8 codes of k-tile 2c and the 8 of k-tile 2c + 1
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const uint4 slot = codes[i];
+  const size_t pair = i >> 6, lane = i & 63;
+  tiles[(2 * pair) * 64 + lane] = e4m3_slot_half(slot, 0);
+  tiles[(2 * pair + 1) * 64 + lane] = e4m3_slot_half(slot, 1);
+}
+
 }  // namespace
+
+void launch_expand_e4m3(const uint4* codes, uint4* tiles, size_t n_slots, hipStream_t st) {
+  const size_t n = n_slots * 64;
+  hipLaunchKernelGGL(expand_e4m3_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, codes, tiles, n);
+}
 
 void launch_gemm_tall(bool f16, int epi, GemmArgs& a, int rows_cap, int S_max, hipStream_t st) {
   a.S = (epi == EPI_RESID && S_max > 1) ? S_max : 1;

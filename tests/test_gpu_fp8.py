@@ -117,3 +117,37 @@ def test_7b_shape_three_layers_with_e4m3_weights():
             assert gt[0].tolist() == toks
     finally:
         gm.close()
+
+
+def test_many_rows_with_e4m3_weights():
+    """16 streams at once: 1280 rows go to the many-rows GEMM, which has no variant for the
+    codes and gets every matrix expanded to fp16 before its launch; a full and a sparse
+    prefill against the oracle on the quantised weights."""
+    prev, cur, redrawn, e_prev, e_cur = tiny_inputs(seed=0)
+    om = oracle_model(TINY, seed=0, std=0.05, w8=True)
+    B = 16
+    gm = GpuModel(TINY, seed=0, max_batch=B, max_seq=96, std=0.05, operand="f16w8")
+    try:
+        cache_p, cache_c = O.new_cache(TINY, 96), O.new_cache(TINY, 96)
+        want_p = O.dense_forward(om, e_prev, 64, cache_p)
+        want_c = O.dense_forward(om, e_cur, 64, cache_c)
+        got = gm.prefill(np.stack([e_prev, e_cur] * (B // 2)), 64)
+        for b in range(B):
+            want = want_p if b % 2 == 0 else want_c
+            assert np.abs(got["hidden"][b] - want["hidden"]).max() <= TOL, b
+            assert np.abs(got["logits"][b] - want["logits"]).max() <= TOL, b
+        # every stream moves on to the current frame: the even ones reuse the static tokens of
+        # the frame pair, the odd ones (same frame again) every second token
+        p_static = O.select_static(prev, cur, 14, 249, 250, 32)
+        want_s = O.sparse_forward(om, e_cur, 64, cache_p, [p_static] * TINY.n_layers)
+        half = list(range(0, 64, 2))
+        got2 = gm.prefill(np.stack([e_cur] * B), 64, [list(p_static) if b % 2 == 0 else half for b in range(B)])
+        alive = ~np.isnan(want_s["hidden"][:, 0])
+        for b in range(B):
+            if b % 2 == 0:
+                assert np.abs(got2["hidden"][b][alive] - want_s["hidden"][alive]).max() <= TOL, b
+                assert np.abs(got2["logits"][b] - want_s["logits"]).max() <= TOL, b
+            else:
+                assert np.abs(got2["logits"][b] - want_c["logits"]).max() <= TOL, b
+    finally:
+        gm.close()
