@@ -44,6 +44,7 @@ struct AttnArgs {
   int* stat_counters;   // [B]
   int defer_stats;      // the parked sums are added up by stats_reduce_kernel after the last layer
   int rows4_from;       // > 0: streams with at least this many rows are left to attn_rows4_kernel
+  int dec_pack;         // decode with grouped queries: the query heads of one kv head share a workgroup
 };
 
 template <int HD, bool F16>
@@ -55,16 +56,23 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a) {
   __shared__ int s_last;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int j = lane & 31, g = lane >> 5;
-  const int b = blockIdx.z, h = blockIdx.y;
+  const int b = blockIdx.z;
   const bool dec = a.decode_pos >= 0;
   const int off_b = dec ? b : a.slot_off[b];
   const int n_b = dec ? 1 : a.slot_off[b + 1] - off_b;
   const int s0 = blockIdx.x * 32;
   if (s0 >= n_b) return;
   if (a.rows4_from > 0 && n_b >= a.rows4_from) return;
-  const int hk = h / (a.n_q_heads / a.n_kv_heads);
-  const bool valid = s0 + j < n_b;
-  const int sg = off_b + (valid ? s0 + j : n_b - 1);  // this lane's query slot
+  // A decode pass has one query per stream and head, 1 column of the 32 a tile has.  With
+  // grouped queries the heads that share a kv head fill the columns of ONE tile (blockIdx.y
+  // is then the kv head, and the head is per lane): one workgroup per stream and kv head
+  // reads the K and V tiles that group-many workgroups would each have read.
+  const bool packed = dec && a.dec_pack;
+  const int group = a.n_q_heads / a.n_kv_heads;
+  const int hk = packed ? blockIdx.y : blockIdx.y / group;
+  const int h = packed ? hk * group + min(j, group - 1) : blockIdx.y;
+  const bool valid = packed ? j < group : s0 + j < n_b;
+  const int sg = off_b + ((valid && !packed) ? s0 + j : n_b - 1);  // this lane's query slot
   const int pos = dec ? a.decode_pos : (valid ? (a.rows[sg] & 0xffff) : 0);
   const int pos_last = dec ? a.decode_pos : (a.rows[off_b + min(s0 + 31, n_b - 1)] & 0xffff);
   const int n_kt = (pos_last >> 5) + 1;
@@ -619,7 +627,9 @@ void launch_attention(vlac_ctx* c, int layer, int B, int rows_cap_per_stream, in
       else hipLaunchKernelGGL((attn_rows4_kernel<64, false>), grid4, dim3(256), 0, st, a);
     }
   }
-  dim3 grid((rows_cap_per_stream + 31) / 32, m.n_q_heads, B);
+  const int group = m.n_q_heads / m.n_kv_heads;
+  a.dec_pack = decode_pos >= 0 && group > 1 && group <= 32;
+  dim3 grid((rows_cap_per_stream + 31) / 32, a.dec_pack ? m.n_kv_heads : m.n_q_heads, B);
   if (m.head_dim == 128) {
     if (c->f16) hipLaunchKernelGGL((attn_rows_kernel<128, true>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((attn_rows_kernel<128, false>), grid, dim3(256), 0, st, a);
