@@ -298,6 +298,7 @@ __global__ __launch_bounds__(256, 3) void attn_rows4_kernel(AttnArgs a) {
   constexpr int AHEAD = 2;         // key tiles on their way to LDS while one is worked on (1 and 3: no faster)
   constexpr int NBUF = AHEAD + 1;
   __shared__ uint4 kvs[NBUF][2][TILE];  // [buffer][K, V]
+  __shared__ int s_text[4];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int j = lane & 31, g = lane >> 5;
   const int b = blockIdx.z, h = blockIdx.y;
@@ -307,8 +308,10 @@ __global__ __launch_bounds__(256, 3) void attn_rows4_kernel(AttnArgs a) {
   // tiles: 9 workgroups of 3 or 4, not 8 of 4 and one with a single busy wave)
   const int n_qt = (n_b + 31) >> 5, n_wg = (n_qt + 3) >> 2;
   if ((int)blockIdx.x >= n_wg || n_b < a.rows4_from) return;
-  const int qt_end = ((int)blockIdx.x + 1) * n_qt / n_wg;
-  const int qt = (int)blockIdx.x * n_qt / n_wg + w, s0 = qt * 32;  // this wave's query tile
+  // (the workgroup of the stream's last queries has the longest walk and starts first)
+  const int xb = n_wg - 1 - (int)blockIdx.x;
+  const int qt_end = (xb + 1) * n_qt / n_wg;
+  const int qt = xb * n_qt / n_wg + w, s0 = qt * 32;  // this wave's query tile
   const bool active = qt < qt_end;
   const int hk = h / (a.n_q_heads / a.n_kv_heads);
   const bool valid = active && s0 + j < n_b;
@@ -489,27 +492,49 @@ __global__ __launch_bounds__(256, 3) void attn_rows4_kernel(AttnArgs a) {
   const int x_first = (n_b - a.L_t) >> 5;  // first query tile that holds a text row
   const bool text_wave = active && pos_last >= a.L_v;
   const bool is_text = valid && pos >= a.L_v;
-  float* park = a.statp + (((size_t)b * a.n_q_heads + h) * a.TT + (qt - x_first)) * a.lv_pad;
   const int n_vt = (a.L_v + 31) >> 5;
-  // (all waves are past their last read of the buffers: the loop ended on a barrier)
-  uint4 kr[PER];  // the next K tile on its way to LDS
+  // The waves that hold text rows publish their query fragments, reference points and 1/sums
+  // in LDS (all waves are past their last read of the buffers: the loop ended on a barrier);
+  // then the 4 waves deal the vision key tiles of every such query tile among themselves,
+  // each reading its K tiles straight from global memory: the workgroup with a stream's last
+  // queries, which has the longest walk anyway, adds n_vt / 4 steps to it, not n_vt.
+  uint4* q_sh = &kvs[0][0][0];                   // [4][NC][64]
+  float* f_sh = (float*)(q_sh + 4 * NC * 64);    // [4][3][64]: reference point, 1/sum, text row?
+  static_assert(4 * NC * 64 + 3 * 64 <= NBUF * 2 * TILE, "the buffers hold what the waves publish");
+  if (text_wave) {
 #pragma unroll
-  for (int u = 0; u < PER; ++u) kvs[0][0][tid + 256 * u] = ksrc[256 * u];
+    for (int c = 0; c < NC; ++c) q_sh[(w * NC + c) * 64 + lane] = qf[c];
+    f_sh[(w * 3 + 0) * 64 + lane] = m;
+    f_sh[(w * 3 + 1) * 64 + lane] = inv;
+    f_sh[(w * 3 + 2) * 64 + lane] = is_text ? 1.f : 0.f;
+  }
+  if (lane == 0) s_text[w] = text_wave ? 1 : 0;
   __syncthreads();
-  for (int kt = 0; kt < n_vt; ++kt) {
-    const int buf = kt & 1;
-    const size_t nx = (size_t)min(kt + 1, n_vt - 1) * TILE;
+  const bf16_t* kbase = a.kv + (size_t)b * a.kv_stream_stride + (size_t)hk * head_elems + (size_t)lane * 8;
+  auto load_k = [&](int kt, uint4(&kf)[NC]) {
 #pragma unroll
-    for (int u = 0; u < PER; ++u) kr[u] = ksrc[nx + 256 * u];
-    if (text_wave) {
+    for (int c = 0; c < NC; ++c) kf[c] = *(const uint4*)(kbase + ((size_t)kt * NC + c) * 512);
+  };
+  for (int tw = 0; tw < 4; ++tw) {
+    if (!s_text[tw]) continue;
+    uint4 qt_f[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) qt_f[c] = q_sh[(tw * NC + c) * 64 + lane];
+    const float m_t = f_sh[(tw * 3 + 0) * 64 + lane], inv_t = f_sh[(tw * 3 + 1) * 64 + lane];
+    const bool txt = f_sh[(tw * 3 + 2) * 64 + lane] != 0.f;
+    float* park = a.statp + (((size_t)b * a.n_q_heads + h) * a.TT + (qt - w + tw - x_first)) * a.lv_pad;
+    uint4 kf[NC], kn[NC];
+    if (w < n_vt) load_k(w, kf);
+    for (int kt = w; kt < n_vt; kt += 4) {
+      if (kt + 4 < n_vt) load_k(kt + 4, kn);
       f32x16 s;
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
-      for (int c = 0; c < NC; ++c) s = mfma32<F16>(kvs[buf][0][c * 64 + lane], qf[c], s);
+      for (int c = 0; c < NC; ++c) s = mfma32<F16>(kf[c], qt_f[c], s);
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        float pv = is_text ? exp2f(s[i] * a.scale_log2e - m) * inv : 0.f;
+        float pv = txt ? exp2f(s[i] * a.scale_log2e - m_t) * inv_t : 0.f;
         // sum over the 32 queries of the tile (the lanes of a half-wave), fixed order
 #pragma unroll
         for (int d = 1; d < 32; d <<= 1) pv += __shfl_xor(pv, d);
@@ -521,10 +546,9 @@ __global__ __launch_bounds__(256, 3) void attn_rows4_kernel(AttnArgs a) {
           *(float4*)(park + 32 * kt + 8 * q4 + 4 * g) =
               make_float4(s[4 * q4], s[4 * q4 + 1], s[4 * q4 + 2], s[4 * q4 + 3]);
       }
-    }
 #pragma unroll
-    for (int u = 0; u < PER; ++u) kvs[buf ^ 1][0][tid + 256 * u] = kr[u];
-    __syncthreads();
+      for (int c = 0; c < NC; ++c) kf[c] = kn[c];
+    }
   }
 }
 
