@@ -301,15 +301,19 @@ __global__ __launch_bounds__(256, 3) void attn_rows4_kernel(AttnArgs a) {
   __shared__ int s_text[4];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int j = lane & 31, g = lane >> 5;
-  const int b = blockIdx.z, h = blockIdx.y;
+  // grid (heads, streams, query blocks): the query block is the slowest index, see below
+  const int b = blockIdx.y, h = blockIdx.x;
   const int off_b = a.slot_off[b];
   const int n_b = a.slot_off[b + 1] - off_b;
   // the stream's query tiles are dealt to its workgroups in equal shares of at most 4 (33
   // tiles: 9 workgroups of 3 or 4, not 8 of 4 and one with a single busy wave)
   const int n_qt = (n_b + 31) >> 5, n_wg = (n_qt + 3) >> 2;
-  if ((int)blockIdx.x >= n_wg || n_b < a.rows4_from) return;
-  // (the workgroup of the stream's last queries has the longest walk and starts first)
-  const int xb = n_wg - 1 - (int)blockIdx.x;
+  if ((int)blockIdx.z >= n_wg || n_b < a.rows4_from) return;
+  // The workgroups of the streams' LAST queries have the longest walks, and the launch lasts
+  // as long as the last of them: they start first, those of ALL streams and heads before any
+  // shorter one (the heads are the fastest index: workgroup id % 8, the XCD, is then the
+  // same for all workgroups of a stream and head, which share its K and V in that L2).
+  const int xb = n_wg - 1 - (int)blockIdx.z;
   const int qt_end = (xb + 1) * n_qt / n_wg;
   const int qt = xb * n_qt / n_wg + w, s0 = qt * 32;  // this wave's query tile
   const bool active = qt < qt_end;
@@ -523,10 +527,12 @@ __global__ __launch_bounds__(256, 3) void attn_rows4_kernel(AttnArgs a) {
     const float m_t = f_sh[(tw * 3 + 0) * 64 + lane], inv_t = f_sh[(tw * 3 + 1) * 64 + lane];
     const bool txt = f_sh[(tw * 3 + 2) * 64 + lane] != 0.f;
     float* park = a.statp + (((size_t)b * a.n_q_heads + h) * a.TT + (qt - w + tw - x_first)) * a.lv_pad;
-    uint4 kf[NC], kn[NC];
+    // (a wave's K tiles are requested two tiles ahead: the pass is a chain of round trips to memory)
+    uint4 kf[NC], kn[NC], kn2[NC];
     if (w < n_vt) load_k(w, kf);
+    if (w + 4 < n_vt) load_k(w + 4, kn);
     for (int kt = w; kt < n_vt; kt += 4) {
-      if (kt + 4 < n_vt) load_k(kt + 4, kn);
+      if (kt + 8 < n_vt) load_k(kt + 8, kn2);
       f32x16 s;
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[i] = 0.f;
@@ -547,7 +553,10 @@ __global__ __launch_bounds__(256, 3) void attn_rows4_kernel(AttnArgs a) {
               make_float4(s[4 * q4], s[4 * q4 + 1], s[4 * q4 + 2], s[4 * q4 + 3]);
       }
 #pragma unroll
-      for (int c = 0; c < NC; ++c) kf[c] = kn[c];
+      for (int c = 0; c < NC; ++c) {
+        kf[c] = kn[c];
+        kn[c] = kn2[c];
+      }
     }
   }
 }
@@ -642,7 +651,7 @@ void launch_attention(vlac_ctx* c, int layer, int B, int rows_cap_per_stream, in
   if (decode_pos < 0 && rows_cap_per_stream >= 512 && (long long)groups * m.n_q_heads * B >= 512 &&
       (!a.attn_mean || a.defer_stats)) {
     a.rows4_from = 256;
-    dim3 grid4(groups, m.n_q_heads, B);
+    dim3 grid4(m.n_q_heads, B, groups);
     if (m.head_dim == 128) {
       if (c->f16) hipLaunchKernelGGL((attn_rows4_kernel<128, true>), grid4, dim3(256), 0, st, a);
       else hipLaunchKernelGGL((attn_rows4_kernel<128, false>), grid4, dim3(256), 0, st, a);
