@@ -640,17 +640,20 @@ void launch_attention(vlac_ctx* c, int layer, int B, int rows_cap_per_stream, in
     a.statp = c->statp;
   }
   a.stat_counters = c->stat_counters;
-  // Long sequences of many streams (work for every CU several times over): streams with at
-  // least 256 rows to recompute go to the kernel with one query tile per WAVE, where the 4
-  // waves of a workgroup share K and V; streams with fewer rows (and every other shape) to the
-  // kernel with one query tile per workgroup and the key tiles dealt to its waves, which has
-  // the shorter critical path.  The row counts are known on the device only, so both
-  // kernels are launched and each leaves the other's streams alone.
+  // Long sequences of many streams (work for every CU several times over): streams with more
+  // than two query tiles to recompute (65 rows) go to the kernel with one query tile per
+  // WAVE, where the 4 waves of a workgroup share K and V (the cache is read once per 128
+  // queries and not once per 32: measured at 8 streams x 1056 tokens, 134 rows per stream:
+  // 4.2 ms per 32-layer prefill outside the GEMMs against 5.7 ms); streams with fewer rows
+  // (and every other shape) to the kernel with one query tile per workgroup and the key
+  // tiles dealt to its waves, which has the shorter critical path.  The row counts are
+  // known on the device only, so both kernels are launched and each leaves the other's
+  // streams alone.
   const int groups = (rows_cap_per_stream + 127) / 128;
   a.rows4_from = 0;
   if (decode_pos < 0 && rows_cap_per_stream >= 512 && (long long)groups * m.n_q_heads * B >= 512 &&
       (!a.attn_mean || a.defer_stats)) {
-    a.rows4_from = 256;
+    a.rows4_from = 65;
     dim3 grid4(m.n_q_heads, B, groups);
     if (m.head_dim == 128) {
       if (c->f16) hipLaunchKernelGGL((attn_rows4_kernel<128, true>), grid4, dim3(256), 0, st, a);
