@@ -204,17 +204,18 @@ def test_hires_batched_shape_against_oracle():
 
 
 def test_hires_batched_streams_with_few_and_many_rows():
-    """The same shape with one stream 70% static (339 rows to recompute) and one 93% static
-    (about 100 rows): the two attention kernels for long sequences (one query tile per wave
-    for streams with many rows, one per workgroup for the others) share a launch pair."""
-    _check_streams(CFG.with_layers(1), B=2, n_vis=1024, n_txt=32, static_frac=np.array([[0.7], [0.93]]),
+    """The same shape with one stream 70% static (339 rows to recompute) and one 97% static
+    (about 60 rows): the two attention kernels for long sequences (one query tile per wave
+    for streams with 65 rows or more, one per workgroup for the others) share a launch pair."""
+    _check_streams(CFG.with_layers(1), B=2, n_vis=1024, n_txt=32, static_frac=np.array([[0.7], [0.97]]),
                    seed=13, n_new=1)
 
 
 def test_gqa_batched_shape_against_oracle():
     """Grouped-query shape: d 1536, 12 query / 2 kv heads x 128, FFN 8960, rope base 1e6,
-    256 visual + 48 text tokens, 75% static; 8 streams x 2 layers against the oracle."""
-    _check_streams(synth.CONFIGS["gqa"].with_layers(2), B=8, n_vis=256, n_txt=48, static_frac=0.75,
+    256 visual + 48 text tokens, 75% static; 16 streams x 2 layers against the oracle (16
+    streams: enough workgroups for the attention kernel with one query tile per wave)."""
+    _check_streams(synth.CONFIGS["gqa"].with_layers(2), B=16, n_vis=256, n_txt=48, static_frac=0.75,
                    seed=4, n_new=2)
 
 
