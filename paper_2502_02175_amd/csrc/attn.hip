@@ -509,7 +509,7 @@ __global__ __launch_bounds__(256, 3) void attn_rows4_kernel(AttnArgs a) {
 #pragma unroll
     for (int c = 0; c < NC; ++c) q_sh[(w * NC + c) * 64 + lane] = qf[c];
     f_sh[(w * 3 + 0) * 64 + lane] = m;
-    f_sh[(w * 3 + 1) * 64 + lane] = inv;
+    f_sh[(w * 3 + 1) * 64 + lane] = is_text ? inv : 0.f;  // (a row that is no text row adds nothing)
     f_sh[(w * 3 + 2) * 64 + lane] = is_text ? 1.f : 0.f;
   }
   if (lane == 0) s_text[w] = text_wave ? 1 : 0;
@@ -519,44 +519,39 @@ __global__ __launch_bounds__(256, 3) void attn_rows4_kernel(AttnArgs a) {
 #pragma unroll
     for (int c = 0; c < NC; ++c) kf[c] = *(const uint4*)(kbase + ((size_t)kt * NC + c) * 512);
   };
+  // Here the scores are taken the other way round, Q K^T: a lane's column is a KEY and its 16
+  // registers are queries (8 q4 + 4 g + e), so the sum over the queries of a tile is 16
+  // additions in the lane and one exchange between the two halves of the wave.
   for (int tw = 0; tw < 4; ++tw) {
     if (!s_text[tw]) continue;
     uint4 qt_f[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) qt_f[c] = q_sh[(tw * NC + c) * 64 + lane];
-    const float m_t = f_sh[(tw * 3 + 0) * 64 + lane], inv_t = f_sh[(tw * 3 + 1) * 64 + lane];
-    const bool txt = f_sh[(tw * 3 + 2) * 64 + lane] != 0.f;
+    // per register: its query's reference point and 1/sum (0: no text row), read from LDS
+    // where they are needed (they would cost 32 registers next to three K tiles)
+    const float* m_q = f_sh + (tw * 3 + 0) * 64 + 4 * g;
+    const float* inv_q = f_sh + (tw * 3 + 1) * 64 + 4 * g;
     float* park = a.statp + (((size_t)b * a.n_q_heads + h) * a.TT + (qt - w + tw - x_first)) * a.lv_pad;
-    // (a wave's K tiles are requested two tiles ahead: the pass is a chain of round trips to memory)
-    uint4 kf[NC], kn[NC], kn2[NC];
+    uint4 kf[NC], kn[NC];
     if (w < n_vt) load_k(w, kf);
-    if (w + 4 < n_vt) load_k(w + 4, kn);
     for (int kt = w; kt < n_vt; kt += 4) {
-      if (kt + 8 < n_vt) load_k(kt + 8, kn2);
+      if (kt + 4 < n_vt) load_k(kt + 4, kn);
       f32x16 s;
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
-      for (int c = 0; c < NC; ++c) s = mfma32<F16>(kf[c], qt_f[c], s);
+      for (int c = 0; c < NC; ++c) s = mfma32<F16>(qt_f[c], kf[c], s);
+      float r = 0.f;  // fixed order: the lane's 16 queries, then the other half's
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        float pv = txt ? exp2f(s[i] * a.scale_log2e - m_t) * inv_t : 0.f;
-        // sum over the 32 queries of the tile (the lanes of a half-wave), fixed order
-#pragma unroll
-        for (int d = 1; d < 32; d <<= 1) pv += __shfl_xor(pv, d);
-        s[i] = pv;
+        const int qi = 8 * (i >> 2) + (i & 3);
+        const float iq = inv_q[qi];
+        r += iq != 0.f ? exp2f(s[i] * a.scale_log2e - m_q[qi]) * iq : 0.f;
       }
-      if (j == 0) {
+      r += __shfl_xor(r, 32);
+      if (g == 0) park[32 * kt + j] = r;
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4)
-          *(float4*)(park + 32 * kt + 8 * q4 + 4 * g) =
-              make_float4(s[4 * q4], s[4 * q4 + 1], s[4 * q4 + 2], s[4 * q4 + 3]);
-      }
-#pragma unroll
-      for (int c = 0; c < NC; ++c) {
-        kf[c] = kn[c];
-        kn[c] = kn2[c];
-      }
+      for (int c = 0; c < NC; ++c) kf[c] = kn[c];
     }
   }
 }
