@@ -183,7 +183,7 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a) {
     }
     const float inv = 1.f / l;
     fin[0][lane] = m;
-    fin[1][lane] = inv;
+    fin[1][lane] = (valid && pos >= a.L_v) ? inv : 0.f;  // (the statistic counts text rows only)
     if (valid) {
 #pragma unroll
       for (int ib = 0; ib < NI; ++ib)
@@ -201,36 +201,36 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a) {
   if (!a.attn_mean || a.L_t <= 0 || a.L_v <= 0 || dec) return;
   if (pos_last < a.L_v) return;  // no text row in this tile
   __syncthreads();
-  const float m_fin = fin[0][lane], inv_fin = fin[1][lane];
   const int x_first = (n_b - a.L_t) >> 5;  // first tile that holds a text row
   const int n_tt = ((n_b - 1) >> 5) - x_first + 1;
   const int tt = blockIdx.x - x_first;
-  const bool is_text = valid && pos >= a.L_v;
   float* park = a.statp + (((size_t)b * a.n_q_heads + h) * a.TT + tt) * a.lv_pad;
   const int n_vt = (a.L_v + 31) >> 5;
+  // Here the scores are taken the other way round, Q K^T: a lane's column is a KEY and its 16
+  // registers are queries (8 q4 + 4 g + e, whose reference point and 1/sum wave 0 left in
+  // LDS), so the sum over the queries of the tile is 16 additions in the lane and one
+  // exchange between the two halves of the wave.
+  const float* m_q = fin[0] + 4 * g;
+  const float* inv_q = fin[1] + 4 * g;
   if (w < n_vt) load_k(w, kf);
   for (int kt = w; kt < n_vt; kt += 4) {
     f32x16 s;
-    scores(kf, s);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) s = mfma32<F16>(qf[c], kf[c], s);
     if (kt + 4 < n_vt) load_k(kt + 4, kf);  // the next tile flies during the arithmetic
+    float r = 0.f;  // fixed order: the lane's 16 queries, then the other half's
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      float pv = is_text ? exp2f(s[i] * a.scale_log2e - m_fin) * inv_fin : 0.f;
-      // sum over the 32 queries of the tile (the lanes of a half-wave), fixed order
-#pragma unroll
-      for (int d = 1; d < 32; d <<= 1) pv += __shfl_xor(pv, d);
-      s[i] = pv;
+      const int qi = 8 * (i >> 2) + (i & 3);
+      const float iq = inv_q[qi];
+      r += iq != 0.f ? exp2f(s[i] * a.scale_log2e - m_q[qi]) * iq : 0.f;
     }
-    if (j == 0) {
-      if (a.defer_stats) {  // read by a later kernel: plain stores
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4)
-          *(float4*)(park + 32 * kt + 8 * q4 + 4 * g) =
-              make_float4(s[4 * q4], s[4 * q4 + 1], s[4 * q4 + 2], s[4 * q4 + 3]);
-      } else {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) st_coherent(park + 32 * kt + 8 * (i >> 2) + 4 * g + (i & 3), s[i]);
-      }
+    r += __shfl_xor(r, 32);
+    if (g == 0) {
+      if (a.defer_stats) park[32 * kt + j] = r;  // read by a later kernel: plain stores
+      else st_coherent(park + 32 * kt + j, r);
     }
   }
   if (a.defer_stats) return;
