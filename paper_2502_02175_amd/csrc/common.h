@@ -262,6 +262,19 @@ __host__ __device__ inline TallPlan tall_plan(int n_blocks, int row_blocks, int 
   best.tiles = (n_blocks + 15) >> 4;
   best.S = 1;
   const int items2 = best.tiles * row_blocks;
+  if (items2 > 256) {
+    // More than one round of 256 items: the narrow tiles only where they save most of a round
+    // (a little more than one round of wide items takes two: 301 items of cost 1 against
+    // 602 of cost 0.575 in three rounds), with a margin, because short items of ragged row
+    // blocks fill gaps that this count of rounds does not see.
+    const int tiles1 = (n_blocks + 7) >> 3;
+    const int cost_w = ((items2 + 255) >> 8) * 200, cost_n = ((tiles1 * row_blocks + 255) >> 8) * 115;
+    if (cost_n * 11 < cost_w * 10) {
+      best.nf = 1;
+      best.tiles = tiles1;
+    }
+    return best;
+  }
   if (items2 > 128 || items2 < 1) return best;  // no other cut fits into one round of 256 items
   // Less than one work item per two CUs: of the cuts that still give at most 256 items, take
   // the one with the least estimated item time (in integers, so that host and device agree):
