@@ -546,7 +546,8 @@ def two_views_chunk(args, V, GpuModel, np, torch, synth, dev):
     ctx, kv = gm.ctx, gm.kv
     stats = [torch.zeros((nl, 1, n_vis), device=dev) for _ in range(2)]
     i32 = dict(dtype=torch.int32, device=dev)
-    idx, order = torch.zeros((1, n_vis), **i32), torch.zeros((1, n_vis), **i32)
+    # (lists of top_k entries: their length also tells the library how few rows a pass can have)
+    idx, order = torch.zeros((1, top_k), **i32), torch.zeros((1, top_k), **i32)
     cnt, tok = torch.zeros(1, **i32), torch.zeros(1, **i32)
     hidden = torch.zeros((1, L, cfg.d_model), device=dev)
     V.vlac_sparse_prefill(ctx, emb[0], 1, n_vis, L_t, None, None, 1, None, kv, stats[0], hidden, None, tok)
@@ -556,9 +557,9 @@ def two_views_chunk(args, V, GpuModel, np, torch, synth, dev):
         e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
         e[0].record()
         V.vlac_select_static(ctx, d_frames[t - 1], d_frames[t], 1, 2 * H, H, patch, 249, 250, top_k, a,
-                             None, tau_task, idx, order, cnt, None, n_vis)
+                             None, tau_task, idx, order, cnt, None, top_k)
         e[1].record()
-        V.vlac_sparse_prefill(ctx, emb[t], 1, n_vis, L_t, order, cnt, n_vis, None, kv, b, hidden, None, tok)
+        V.vlac_sparse_prefill(ctx, emb[t], 1, n_vis, L_t, order, cnt, top_k, None, kv, b, hidden, None, tok)
         e[2].record()
         torch.cuda.synchronize()
         if t >= warm:

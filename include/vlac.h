@@ -220,6 +220,9 @@ int vlac_layer_ratio(vlac_ctx* ctx, const float* attn_mean, int B, int L_v, floa
  *
  * reuse_order: device int32 [B, stride]; reuse_count: device int32 [B], or both
  * NULL for a full recompute (required for a stream after vlac_reset_stream).
+ * Counts above stride are clamped to stride (and reported, see vlac_check).  stride is also
+ * what the host knows of the row count (at least B (L - stride) rows are recomputed) when
+ * it chooses the kernels of a launch: pass lists no longer than the selection's top_k.
  * Entries outside [0, L_v) and repeated entries are ignored (see vlac_check).
  * layer_count: device int32 [B, n_layers] or NULL (= reuse_count at every layer).
  *

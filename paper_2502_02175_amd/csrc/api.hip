@@ -655,6 +655,8 @@ int vlac_sparse_prefill(vlac_ctx* ctx, const float* embeds, int B, int L_v, int 
   launch_plan(ctx, B, L_v, L_t, reuse_order, reuse_count, stride, layer_count, st);
   const int rows_cap = B * L;
   const int n_host = reuse_order ? -1 : rows_cap;
+  // (a stream reuses at most `stride` tokens: its list has no room for more)
+  ctx->rows_floor = reuse_order ? B * (L - (stride < L_v ? stride : L_v)) : rows_cap;
   int pending = 0;
   for (int l = 0; l < nl; ++l) {
     const int* rows = ctx->rows + (size_t)l * ctx->max_rows;

@@ -98,6 +98,9 @@ struct LayerW {
 struct SplitAdapt {
   const int* n_rows;  // device: the row count the GEMM ran with (n_rows_host >= 0: not read)
   int n_rows_host, n_blocks, KS;  // the GEMM's feature blocks and 64-k steps
+  int S_tall;         // most splits the many-rows kernel may have used
+  int small_below;    // > 0: with fewer rows than this the one-stream kernel ran instead ...
+  int S_small;        // ... and split K in this many parts (1: it completed the rows itself)
 };
 
 struct vlac_ctx {
@@ -118,6 +121,7 @@ struct vlac_ctx {
   float* s_head;
   float* scale_tmp;  // scales in source row order while a matrix is being packed
   bf16_t* wdeq;      // e4m3 weights, many rows: one matrix expanded to fp16 for the many-rows GEMM
+  int rows_floor;    // fewest rows the prefill that is being launched can have (from the reuse lists' length)
   SplitAdapt pending_adapt;  // of the FFN-down GEMM whose partial rows the next layer's first row kernel adds
   float* g_final;
   float *rope_cos, *rope_sin;  // [max_seq, hd/2]

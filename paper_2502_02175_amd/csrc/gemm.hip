@@ -264,7 +264,7 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(GemmArgs a) {
   }
   const int n_rows = a.n_rows_val >= 0 ? a.n_rows_val : *a.n_rows;
   const int row0 = mb * MT * 32;
-  if (row0 >= n_rows) return;
+  if (row0 >= n_rows || n_rows >= a.rows_hi) return;  // (rows_hi and more: the many-rows kernel's share)
   static_assert(MT == 4, "row blocks are 4 tiles of 32 rows");
   switch (min(MT, (n_rows - row0 + 31) >> 5)) {
     case 1: rows_body<1, MT, EPI, F16, W8>(a, lds, &s_last, tile, s, mb, n_rows, pf0, pf1); break;
@@ -600,15 +600,74 @@ static int tall_resid_smax(const vlac_ctx* c, int epi, int rows_cap, int d_model
   return (size_t)3 * rows_cap * d_model <= c->rpart_floats ? 3 : 1;
 }
 
+// Split factor of the one-stream kernel (row blocks of 128 rows, MB of them in the grid).
+// Split K so that ONE row block (the sparse prefill usually fills one; a full recompute
+// runs several side by side) gives about one workgroup per CU.  The projections with
+// a residual round up (their splits cost next to nothing: the row kernel that follows
+// adds the partial rows); the others round DOWN: their split-K hand-over at the end of
+// the kernel costs more than leaving a third of the CUs without a workgroup (measured
+// at the 7B shape, 109 rows: gate/up with 172 tiles 52 us unsplit against 63 us in two
+// splits; QKV with 96 tiles 42 us in two splits against 52 us in three).
+static int rows_kernel_splits(const vlac_ctx* c, int epi, int n_blocks, int KS, int MB, int rpart_rows, int d_model) {
+  const int tiles = (n_blocks + 3) / 4;
+  int S = epi == EPI_RESID ? (256 + tiles - 1) / tiles : 256 / tiles;
+  if (S > KS / 4) S = KS / 4;
+  if (S > 8) S = 8;
+  if (S < 1) S = 1;
+  if (epi == EPI_RESID) {
+    while (S > 1 && (size_t)S * rpart_rows * d_model > c->rpart_floats) --S;
+  } else {
+    while (S > 1 && (size_t)tiles * MB * S * 4 * 4 * 16 * 64 > c->partial_floats) --S;
+    if (tiles * MB > c->n_counters) S = 1;
+  }
+  return S;
+}
+
+// Where the many-rows kernel serves a capacity at which a sparse prefill usually leaves
+// fewer than kSmallRows rows (the count is known on the device only), BOTH kernels are
+// launched for a GEMM and each leaves at once if the count is the other's.  Measured at
+// the 7B shape, two streams of 288 tokens: 116 rows 5.6 against 7.9 ms per 32-layer
+// prefill, 218 rows 7.3 against 7.8 ms, and 0.4 ms more where the many-rows kernel works
+// (128 idle launches of 3 us); at 70 % static about 0.38 of the capacity is recomputed,
+// so from a capacity of 768 rows on the second launch would mostly be the idle one; and
+// where the reuse lists are too short to leave fewer than kSmallRows rows (top-k 100 of two
+// camera views), only the many-rows kernel is launched.
+static const int kSmallRows = 256;
+static bool use_both(const vlac_ctx* c, int rows_cap, int n_rows_host) {
+  return use_tall(c, rows_cap) && !c->w8 && n_rows_host < 0 && rows_cap < 768 && c->rows_floor < kSmallRows;
+}
+
 SplitAdapt gemm_resid_adapt(vlac_ctx* c, int n_blocks, int kpad, int rows_cap, const int* n_rows, int n_rows_host) {
-  SplitAdapt ad = {nullptr, -1, 0, 0};
-  if (use_tall(c, rows_cap) && tall_resid_smax(c, EPI_RESID, rows_cap, n_blocks * 32) > 1) {
+  SplitAdapt ad = {nullptr, -1, 0, 0, 0, 0, 0};
+  if (!use_tall(c, rows_cap)) return ad;
+  const int d_model = n_blocks * 32;
+  const bool both = use_both(c, rows_cap, n_rows_host);
+  ad.S_tall = tall_resid_smax(c, EPI_RESID, rows_cap, d_model);
+  if (ad.S_tall > 1 || both) {
     ad.n_rows = n_rows;
     ad.n_rows_host = n_rows_host;
     ad.n_blocks = n_blocks;
     ad.KS = kpad / 64;
+    if (both) {
+      ad.small_below = kSmallRows;
+      ad.S_small = rows_kernel_splits(c, EPI_RESID, n_blocks, kpad / 64, kSmallRows / 128, rows_cap, d_model);
+    }
   }
   return ad;
+}
+
+// the one-stream kernel for up to rows_cap rows; sets and returns a.S
+static int launch_rows_kernel(vlac_ctx* c, int epi, GemmArgs& a, int rows_cap, const GemmEpi& e, hipStream_t st) {
+  constexpr int MT = 4;
+  const int tiles = (a.NB + 3) / 4;
+  a.MB = (rows_cap + MT * 32 - 1) / (MT * 32);
+  a.S = rows_kernel_splits(c, epi, a.NB, a.KS, a.MB, e.rpart_rows, e.d_model);
+  a.P = tiles * a.S;
+  const int grid = ((a.P + 7) / 8) * 8 * a.MB;
+  if (c->w8) launch_mt<MT, true, true>(epi, a, grid, st);
+  else if (c->f16) launch_mt<MT, true, false>(epi, a, grid, st);
+  else launch_mt<MT, false, false>(epi, a, grid, st);
+  return a.S;
 }
 
 int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, const float* wscale, int n_blocks, int kpad,
@@ -624,6 +683,8 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, const float* wscale, int
   a.KS = kpad / 64;
   a.n_rows = n_rows;
   a.n_rows_val = n_rows_host;
+  a.rows_lo = 0;
+  a.rows_hi = 0x7fffffff;
   memset(&a.norm, 0, sizeof(a.norm));
   if (norm) a.norm = *norm;
   a.partial = c->partial;
@@ -662,38 +723,21 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, const float* wscale, int
       else launch_few<false, X_GLOBAL, false>(epi, a, a.P, 0, st);
     }
   } else if (use_tall(c, rows_cap)) {
+    int S_small = 0;
+    if (use_both(c, rows_cap, n_rows_host)) {
+      GemmArgs r = a;
+      r.rows_hi = kSmallRows;
+      S_small = launch_rows_kernel(c, epi, r, kSmallRows - 1, e, st);
+      a.rows_lo = kSmallRows;
+    }
     if (c->w8) {
       launch_expand_e4m3(a.wp, (uint4*)c->wdeq, (size_t)n_blocks * 2 * a.KS, st);
       a.wp = (const uint4*)c->wdeq;
     }
     launch_gemm_tall(c->f16, epi, a, rows_cap, tall_resid_smax(c, epi, rows_cap, e.d_model), st);
+    if (S_small > a.S) a.S = S_small;  // (the caller learns the most splits either kernel may leave)
   } else {
-    constexpr int MT = 4;
-    const int tiles = (n_blocks + 3) / 4;
-    a.MB = (rows_cap + MT * 32 - 1) / (MT * 32);
-    // Split K so that ONE row block (the sparse prefill usually fills one; a full recompute
-    // runs several side by side) gives about one workgroup per CU.  The projections with
-    // a residual round up (their splits cost next to nothing: the row kernel that follows
-    // adds the partial rows); the others round DOWN: their split-K hand-over at the end of
-    // the kernel costs more than leaving a third of the CUs without a workgroup (measured
-    // at the 7B shape, 109 rows: gate/up with 172 tiles 52 us unsplit against 63 us in two
-    // splits; QKV with 96 tiles 42 us in two splits against 52 us in three).
-    int S = epi == EPI_RESID ? (256 + tiles - 1) / tiles : 256 / tiles;
-    if (S > a.KS / 4) S = a.KS / 4;
-    if (S > 8) S = 8;
-    if (S < 1) S = 1;
-    if (epi == EPI_RESID) {
-      while (S > 1 && (size_t)S * e.rpart_rows * e.d_model > c->rpart_floats) --S;
-    } else {
-      while (S > 1 && (size_t)tiles * a.MB * S * 4 * MT * 16 * 64 > c->partial_floats) --S;
-      if (tiles * a.MB > c->n_counters) S = 1;
-    }
-    a.S = S;
-    a.P = tiles * S;
-    const int grid = ((a.P + 7) / 8) * 8 * a.MB;
-    if (c->w8) launch_mt<MT, true, true>(epi, a, grid, st);
-    else if (c->f16) launch_mt<MT, true, false>(epi, a, grid, st);
-    else launch_mt<MT, false, false>(epi, a, grid, st);
+    launch_rows_kernel(c, epi, a, rows_cap, e, st);
   }
   if (timed) {
     (void)hipEventRecord(c->prof_stop[c->prof_n], st);

@@ -12,6 +12,7 @@ struct GemmArgs {
   int KS;             // K steps (64 k = 4 tiles each)
   const int* n_rows;  // device: rows in use
   int n_rows_val;     // >= 0: the row count is known on the host, n_rows is not read
+  int rows_lo, rows_hi;  // the launch has work only if rows_lo <= row count < rows_hi (two kernels share a GEMM)
   int S, MB, P;       // split-K factor, row blocks, weight tiles * S
   float* partial;
   int* counters;

@@ -204,6 +204,7 @@ __global__ __launch_bounds__(512) void gemm_tall_kernel(GemmArgs a) {
   // (a.S > 1, residual epilogue only: how many K splits are used follows from the row
   // count, see tall_resid_splits)
   const int n_rows = a.n_rows_val >= 0 ? a.n_rows_val : *a.n_rows;
+  if (n_rows < a.rows_lo) return;  // the one-stream kernel's share
   const int MBn = (n_rows + 127) >> 7;
   const TallPlan pl = tall_plan(a.NB, MBn, a.KS, EPI == EPI_RESID ? a.S : 1);
   const int S = pl.S;

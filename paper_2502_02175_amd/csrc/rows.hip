@@ -291,7 +291,7 @@ __global__ __launch_bounds__(256) void resid_norm_rows_kernel(
     // the GEMM chose its split factor from its row count; unsplit, it added to the
     // residual stream itself and left no partial rows
     const int n_g = adapt.n_rows_host >= 0 ? adapt.n_rows_host : *adapt.n_rows;
-    S = tall_plan(adapt.n_blocks, (n_g + 127) >> 7, adapt.KS, S).S;
+    S = n_g < adapt.small_below ? adapt.S_small : tall_plan(adapt.n_blocks, (n_g + 127) >> 7, adapt.KS, adapt.S_tall).S;
     if (S == 1) {
       S = 0;
       r = y;
@@ -398,7 +398,7 @@ void launch_resid_norm_rows(bool f16, const float* resid, int resid_seq_stride, 
                             const int* part_slot, const int* n_rows, int n_rows_host, int max_rows,
                             const float* gain, float eps, int d, bf16_t* xp, int KC,
                             hipStream_t st, const SplitAdapt* adapt) {
-  SplitAdapt ad = {nullptr, -1, 0, 0};
+  SplitAdapt ad = {nullptr, -1, 0, 0, 0, 0, 0};
   if (adapt) ad = *adapt;  // (never given for rows longer than 8192)
 #define VLAC_RN(K)                                                                               \
   hipLaunchKernelGGL(K, dim3(max_rows), dim3(256), 0, st, resid, resid_seq_stride, part, S,      \

@@ -211,6 +211,15 @@ def test_hires_batched_streams_with_few_and_many_rows():
                    seed=13, n_new=1)
 
 
+@pytest.mark.parametrize("static_frac", [0.8, 0.2])
+def test_two_streams_share_a_pass_with_few_or_many_rows(static_frac):
+    """Two 7B-shaped streams of 288 tokens (a capacity of 576 rows, 2 layers): for a GEMM of
+    such a pass both the one-stream and the many-rows kernel are launched, and the row count
+    on the device says which of them works (80% static: 180 rows, the one-stream kernel and
+    its 8 split-K partial rows; 20% static: 470 rows, the many-rows kernel and its plan)."""
+    _check_streams(CFG.with_layers(2), B=2, n_vis=256, n_txt=32, static_frac=static_frac, seed=21, n_new=1)
+
+
 def test_gqa_batched_shape_against_oracle():
     """Grouped-query shape: d 1536, 12 query / 2 kv heads x 128, FFN 8960, rope base 1e6,
     256 visual + 48 text tokens, 75% static; 16 streams x 2 layers against the oracle (16
