@@ -320,7 +320,10 @@ __global__ __launch_bounds__(256, XMODE == X_NORM8 ? 2 : 3) void gemm_few_kernel
   // Loads are unconditional and never touch the loaded data (past the end of the range
   // the weight index is clamped and the activation tile is replaced by a tile of zeros),
   // so the compiler keeps a whole batch in flight behind the MFMAs.  Lanes of rows >=
-  // n_rows read whatever their operand rows hold; their result columns are never stored.
+  // n_rows read the tile of zeros as well (1 KiB that stays in L1): with 8 rows a wave
+  // then fetches 256 bytes of operand rows per k-tile from L2 instead of 1 KiB, as much
+  // as its weight tile.
+  const bool row_lane = (lane & 31) < n_rows;
   auto load = [&](int c, uint4(&b)[U], uint4(&x)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -328,7 +331,7 @@ __global__ __launch_bounds__(256, XMODE == X_NORM8 ? 2 : 3) void gemm_few_kernel
       if constexpr (!W8) b[u] = wsrc[(size_t)cc * 64];
       else if (u < U / 2) b[u] = wsrc[(size_t)max(min((c >> 1) + u, (w_hi >> 1) - 1), 0) * 64];
       if constexpr (XMODE == X_GLOBAL) {
-        const uint4* xs = (c + u < w_hi) ? xsrc + (size_t)cc * 64 : a.zero_tile + lane;
+        const uint4* xs = (c + u < w_hi && row_lane) ? xsrc + (size_t)cc * 64 : a.zero_tile + lane;
         x[u] = *xs;
       }
     }
