@@ -241,6 +241,44 @@ def test_mid_size_split_k_with_layer_varying_reuse():
         gm.close()
 
 
+def test_row_count_crosses_between_the_two_gemm_kernels_over_depth():
+    """Six streams of 80 + 20 tokens at d = 1024 (a capacity of 600 rows: for every GEMM both the
+    one-stream and the many-rows kernel are launched and the row count on the device says
+    which works).  With reuse counts that grow over depth, layers 0 and 1 recompute more
+    than 256 rows, layers 2 and 3 fewer: the partial rows of one kernel's FFN-down GEMM are
+    consumed under the other kernel's layer, in the format of the kernel that wrote them."""
+    cfg = synth.ModelCfg(4, 1024, 8, 8, 128, 2752, 512)
+    om = oracle_model(cfg, seed=15, std=0.03)
+    gm = GpuModel(cfg, seed=15, max_batch=6, max_seq=128, std=0.03)
+    try:
+        rng = np.random.default_rng(3)
+        n_vis, n_txt, B = 80, 20, 6
+        e0 = synth.round_bf16(rng.standard_normal((B, n_vis + n_txt, cfg.d_model)))
+        e1 = e0.copy()
+        changed = rng.random((B, n_vis)) < 0.1
+        e1[:, :n_vis][changed] = synth.round_bf16(rng.standard_normal((int(changed.sum()), cfg.d_model)))
+        caches = [O.new_cache(cfg, 128) for _ in range(B)]
+        for b in range(B):
+            O.dense_forward(om, e0[b], n_vis, caches[b])
+        gm.prefill(e0, n_vis, want_stats=False, want_hidden=False)
+        orders, counts, sets = [], [], []
+        for b in range(B):
+            static = np.flatnonzero(~changed[b]).tolist()
+            rng.shuffle(static)
+            n = len(static)
+            m = [n // 8, n // 2, (7 * n) // 8, n]
+            orders.append(static), counts.append(m)
+            sets.append([static[:k] for k in m])
+        rows = [sum(n_vis + n_txt - counts[b][l] for b in range(B)) for l in range(4)]
+        assert rows[0] > 256 and rows[1] > 256 and rows[2] < 256 and rows[3] < 256, rows
+        want = [O.sparse_forward(om, e1[b], n_vis, caches[b], sets[b]) for b in range(B)]
+        got = gm.prefill(e1, n_vis, orders, counts)
+        for b in range(B):
+            check(got, want[b], b)
+    finally:
+        gm.close()
+
+
 def test_ignored_indices_are_reported(tiny):
     gm = tiny["gm"]
     V, torch = gm.V, gm.torch
