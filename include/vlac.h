@@ -111,6 +111,17 @@ int vlac_set_head_weights(vlac_ctx* ctx, const void* g_final, const void* w_head
  * It persists across control steps: it is the state Alg. 2 carries from t-1 to t. */
 size_t vlac_kv_cache_bytes(const vlac_model_cfg* cfg);
 
+/* How a projection of a batched prefill (Alg. 2 over the rows of many streams: the
+ * many-rows GEMM) cuts its work for a given row count; the kernels decide this on the
+ * device, this is the same rule for inspection and tests.  out_features x k is the weight
+ * matrix, rows the recomputed rows of the launch, max_splits the most K splits the
+ * projection may use (1 unless it adds to the residual stream; at most 3).
+ * Results: features per work item (512 or 256), K splits, work items
+ * (weight tiles x splits x blocks of 128 rows).  Needs neither a context nor a GPU.
+ * VLAC_E_NULL / VLAC_E_RANGE on null pointers or non-positive sizes. */
+int vlac_plan_many_rows_gemm(int out_features, int k, int rows, int max_splits,
+                             int* tile_features, int* k_splits, int* work_items);
+
 /* Zero-fills stream b's part of the cache and marks it "never filled": the next
  * prefill of that stream must be a full one.  Must be called once per stream
  * before its first prefill (the kernels read whole 32-position tiles). */

@@ -50,6 +50,8 @@ def lib():
         vp, i32, f32 = C.c_void_p, C.c_int, C.c_float
         L.vlac_status_string.restype = C.c_char_p
         L.vlac_status_string.argtypes = [i32]
+        L.vlac_plan_many_rows_gemm.restype = C.c_int
+        L.vlac_plan_many_rows_gemm.argtypes = [C.c_int] * 4 + [C.POINTER(C.c_int)] * 3
         L.vlac_kv_cache_bytes.restype = C.c_size_t
         L.vlac_kv_cache_bytes.argtypes = [C.POINTER(ModelCfg)]
         L.vlac_create.argtypes = [C.POINTER(ModelCfg), C.POINTER(vp)]
@@ -121,6 +123,15 @@ def _cfg(cfg, max_batch=None, max_seq=None):
         return cfg
     return ModelCfg(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
                     cfg.d_ffn, cfg.vocab, cfg.rms_eps, cfg.rope_base, max_batch, max_seq)
+
+
+def vlac_plan_many_rows_gemm(out_features, k, rows, max_splits=1):
+    """-> (features per work item, K splits, work items); no GPU needed."""
+    tf, ks, wi = C.c_int(), C.c_int(), C.c_int()
+    st = lib().vlac_plan_many_rows_gemm(out_features, k, rows, max_splits, C.byref(tf), C.byref(ks), C.byref(wi))
+    if st != 0:
+        raise VlacError(st, "vlac_plan_many_rows_gemm")
+    return tf.value, ks.value, wi.value
 
 
 def vlac_kv_cache_bytes(cfg):

@@ -93,6 +93,18 @@ const char* vlac_status_string(int s) {
   }
 }
 
+int vlac_plan_many_rows_gemm(int out_features, int k, int rows, int max_splits,
+                             int* tile_features, int* k_splits, int* work_items) {
+  if (!tile_features || !k_splits || !work_items) return VLAC_E_NULL;
+  if (out_features < 1 || k < 1 || rows < 1 || max_splits < 1) return VLAC_E_RANGE;
+  const int row_blocks = (rows + 127) / 128;
+  const TallPlan pl = tall_plan((out_features + 31) / 32, row_blocks, round_up(k, 64) / 64, max_splits);
+  *tile_features = 256 * pl.nf;
+  *k_splits = pl.S;
+  *work_items = pl.tiles * pl.S * row_blocks;
+  return VLAC_OK;
+}
+
 size_t vlac_kv_cache_bytes(const vlac_model_cfg* cfg) {
   if (!cfg || check_cfg(cfg) != VLAC_OK) return 0;
   return kv_elems_per_stream(*cfg) * cfg->max_batch * sizeof(bf16_t);
