@@ -28,7 +28,9 @@
 //    LDS stores cost 3%), a 256 x 256 tile whose weight tiles are fetched by two waves
 //    each (the second fetch hits L1, but the kernel is 5% slower), a persistent grid that
 //    deals the work items of the actual row count round-robin (2% slower than letting
-//    the hardware dispatch one workgroup per item).  The same 8-wave design with one
+//    the hardware dispatch one workgroup per item), a weight ring of 8 k-tiles instead of
+//    6 (no faster: the loop does not wait for latency), a raised wave priority around
+//    the MFMAs of a k-tile (+-1 %).  The same 8-wave design with one
 //    feature block per wave, up to 8 row tiles and split K, tried for ONE stream's prefill
 //    (33..1023 rows) in place of the 4-wave kernel of gemm.hip, was no faster at any row
 //    count (109 rows: 6.0 vs 5.8 ms per prefill; 248 rows: 8.4 vs 8.2 ms).
