@@ -119,13 +119,14 @@ def test_7b_shape_three_layers_with_e4m3_weights():
         gm.close()
 
 
-def test_many_rows_with_e4m3_weights():
+@pytest.mark.parametrize("B", [8, 16])
+def test_many_rows_with_e4m3_weights(B):
     """16 streams at once: 1280 rows go to the many-rows GEMM, which has no variant for the
-    codes and gets every matrix expanded to fp16 before its launch; a full and a sparse
-    prefill against the oracle on the quantised weights."""
+    codes and gets every matrix expanded to fp16 before its launch (8 streams: 640 rows stay
+    with the one-stream kernel, five row blocks of it); a full and a sparse prefill against
+    the oracle on the quantised weights."""
     prev, cur, redrawn, e_prev, e_cur = tiny_inputs(seed=0)
     om = oracle_model(TINY, seed=0, std=0.05, w8=True)
-    B = 16
     gm = GpuModel(TINY, seed=0, max_batch=B, max_seq=96, std=0.05, operand="f16w8")
     try:
         cache_p, cache_c = O.new_cache(TINY, 96), O.new_cache(TINY, 96)
