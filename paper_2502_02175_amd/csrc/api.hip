@@ -708,6 +708,7 @@ int vlac_decode_action(vlac_ctx* ctx, int B, int L, int n_new, const int32_t* fi
   hipStream_t st = (hipStream_t)stream;
   const int ms = m.max_seq;
   const bool fused = gemm_can_fuse_norm(B, L, ctx->kpad_d) && ctx->rpart_floats >= (size_t)8 * B * m.d_model;
+  if (!fused) launch_decode_plan(ctx, B, L, n_new, st);
   for (int t = 0; t < n_new; ++t) {
     const int32_t* tok = t == 0 ? first_token : ctx->tokens;
     float* logits = out_logits ? out_logits + (size_t)t * m.vocab : ctx->logits;
@@ -721,11 +722,22 @@ int vlac_decode_action(vlac_ctx* ctx, int B, int L, int n_new, const int32_t* fi
       const NormIn n = decode_norm(ctx, B, r, ctx->g_final, false);
       run_head(ctx, B, L + t, logits, lstride, out_tokens + t, n_new, ctx->tokens, st, &n);
     } else {
+      // More than 4 streams: the general layer pass over the rows (b, L + t).  With more than
+      // 32 of them the prefill's GEMM and row kernels serve the pass, and those read the row
+      // list (only the few-rows kernels derive a row from decode_pos): plane t of the decode
+      // row lists.  Their projections with a residual may leave split-K partial rows
+      // (`pending`), which the next layer's first row kernel adds up, and after the last
+      // layer a row kernel without a norm.
       launch_embed_rows(ctx->embed, tok, B, m.d_model, m.vocab, ctx->h, ms, L + t, st);
-      int pending = 0;  // at most 32 rows: the few-rows kernel adds its splits up itself
+      const int* drows = ctx->dec_rows + (size_t)t * m.max_batch;
+      int pending = 0;
       for (int l = 0; l < m.n_layers; ++l)
-        run_layer(ctx, l, B, B, 1, 0, 0, ctx->h, ms, nullptr, nullptr, B, L + t, nullptr, nullptr,
+        run_layer(ctx, l, B, B, 1, 0, 0, ctx->h, ms, drows, nullptr, B, L + t, nullptr, nullptr,
                   (bf16_t*)kv_cache, nullptr, &pending, st);
+      if (pending)
+        launch_resid_norm_rows(ctx->f16, ctx->h, ms, ctx->rpart, pending, B, ctx->h, ms, drows, nullptr,
+                               nullptr, B, B, nullptr, m.rms_eps, m.d_model, ctx->xa, ctx->kpad_d / 16,
+                               st, &ctx->pending_adapt);
       run_head(ctx, B, L + t, logits, lstride, out_tokens + t, n_new, ctx->tokens, st);
     }
   }

@@ -636,8 +636,11 @@ static int rows_kernel_splits(const vlac_ctx* c, int epi, int n_blocks, int KS, 
 // where the reuse lists are too short to leave fewer than kSmallRows rows (top-k 100 of two
 // camera views), only the many-rows kernel is launched.
 static const int kSmallRows = 256;
+// (Rows longer than 8192 elements: the row kernel that adds the partial rows up there takes a
+// fixed split factor, so the choice between two kernels with different factors is not offered.)
 static bool use_both(const vlac_ctx* c, int rows_cap, int n_rows_host) {
-  return use_tall(c, rows_cap) && !c->w8 && n_rows_host < 0 && rows_cap < 768 && c->rows_floor < kSmallRows;
+  return use_tall(c, rows_cap) && !c->w8 && n_rows_host < 0 && rows_cap < 768 && c->rows_floor < kSmallRows &&
+         c->cfg.d_model <= 8192;
 }
 
 SplitAdapt gemm_resid_adapt(vlac_ctx* c, int n_blocks, int kpad, int rows_cap, const int* n_rows, int n_rows_host) {
