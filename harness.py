@@ -8,9 +8,11 @@ import synth
 
 class GpuModel:
     def __init__(self, cfg, seed, max_batch, max_seq, gain_jitter=0.1, std=0.02, device="cuda:0",
-                 gen_device="cpu", operand="f16"):
+                 gen_device="cpu", operand="f16", layer_source=None):
         """gen_device="cpu": the shared reference weights (what the oracle sees);
-        a GPU device: weights drawn on the GPU, for timing runs only."""
+        a GPU device: weights drawn on the GPU, for timing runs only.
+        layer_source: l -> dict of bf16 tensors, in place of synth.make_layer (a test that
+        hands the same generated tensors to the oracle)."""
         import torch
         import paper_2502_02175_amd as V
         self.V, self.torch, self.cfg, self.device = V, torch, cfg, device
@@ -20,9 +22,9 @@ class GpuModel:
                                max_batch, max_seq, {"bf16": 0, "f16": 1, "f16w8": 2}[operand])
         self.ctx = V.vlac_create(self.ccfg)
         for l in range(cfg.n_layers):
-            w = {k: v.to(device) for k, v in
-                 synth.make_layer(cfg, seed, l, std=std, gain_jitter=gain_jitter,
-                                  device=gen_device).items()}
+            src = layer_source(l) if layer_source else synth.make_layer(
+                cfg, seed, l, std=std, gain_jitter=gain_jitter, device=gen_device)
+            w = {k: v.to(device) for k, v in src.items()}
             V.vlac_set_layer_weights(self.ctx, l, w)
             torch.cuda.synchronize()
         hd = {k: v.to(device) for k, v in
