@@ -189,6 +189,27 @@ int vlac_select_static(vlac_ctx* ctx, const uint8_t* frame_prev, const uint8_t* 
                        int32_t* out_idx, int32_t* out_order, int32_t* out_count,
                        float* out_relevance, int stride, void* stream);
 
+/* vlac_select_static for callers that cannot allocate device memory and cannot hold a
+ * context's workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same results bit for bit, but no context: n_layers (of
+ * attn_mean, 1..512; ignored when attn_mean is NULL) is passed directly, and the scratch of
+ * the three kernels (patch terms, scores, flags: 17 bytes per patch) lives in a fixed array
+ * of VLAC_NOALLOC_MAX_PATCHES patches (1.1 MB) that the library's code object places in the
+ * memory of every GPU it is loaded on, until the process ends.  The call makes no
+ * allocation of any kind; B * L_v beyond the limit returns VLAC_E_RANGE (as do the argument
+ * errors of vlac_select_static, with the same statuses), and nothing is queued then.
+ * The address of the array on the current device is looked up on the first call on that
+ * device (and by vlac_create): make one of the two before capturing a graph.
+ * All calls on one GPU share that GPU's array, which keeps the last call's contents (every
+ * call overwrites what it reads, nothing has to be cleared): calls that overlap on one GPU,
+ * on whatever streams, race; order them. */
+#define VLAC_NOALLOC_MAX_PATCHES 65536
+int vlac_select_static_noalloc(const uint8_t* frame_prev, const uint8_t* frame_cur, int B, int H,
+                               int W, int patch, int tau_num, int tau_den, int top_k,
+                               const float* attn_mean, int n_layers, const uint8_t* layer_mask,
+                               float tau_task, int32_t* out_idx, int32_t* out_order,
+                               int32_t* out_count, float* out_relevance, int stride, void* stream);
+
 /* Front end for the visual tokens (beyond Alg. 1, in its spirit: a token whose K/V are
  * reused at the first decoder layer, Alg. 2, needs no input embedding either).  The
  * embedding of patch i of frame_cur is the fixed linear map

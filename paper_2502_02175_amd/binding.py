@@ -67,6 +67,8 @@ def lib():
         L.vlac_profile_bracket_cost.argtypes = [vp, vp, C.POINTER(C.c_double)]
         L.vlac_select_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, f32,
                                          vp, vp, vp, vp, i32, vp]
+        L.vlac_select_static_noalloc.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, i32, vp, f32,
+                                                 vp, vp, vp, vp, i32, vp]
         L.vlac_quantize_e4m3.argtypes = [vp, i32, i32, vp, vp, vp]
         L.vlac_embed_patches.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, i32, vp]
         L.vlac_layer_ratio.argtypes = [vp, vp, i32, i32, f32, vp, vp, vp, vp]
@@ -76,7 +78,7 @@ def lib():
                      "vlac_set_head_weights", "vlac_reset_stream", "vlac_check",
                      "vlac_profile_select", "vlac_profile_read", "vlac_profile_read2",
                      "vlac_profile_bracket_cost",
-                     "vlac_select_static", "vlac_embed_patches", "vlac_quantize_e4m3", "vlac_layer_ratio", "vlac_sparse_prefill",
+                     "vlac_select_static", "vlac_select_static_noalloc", "vlac_embed_patches", "vlac_quantize_e4m3", "vlac_layer_ratio", "vlac_sparse_prefill",
                      "vlac_decode_action"):
             getattr(L, name).restype = i32
         _LIB = L
@@ -221,6 +223,23 @@ def vlac_select_static(ctx, frame_prev, frame_cur, B, H, W, patch, tau_num, tau_
         _ptr(out_count, torch.int32, "out_count"), _ptr(out_relevance, torch.float32, "out_relevance"),
         stride, _stream(stream))
     return _ret(st, "vlac_select_static", check)
+
+
+def vlac_select_static_noalloc(frame_prev, frame_cur, B, H, W, patch, tau_num, tau_den, top_k,
+                               attn_mean, n_layers, layer_mask, tau_task, out_idx, out_order, out_count,
+                               out_relevance, stride, stream=None, check=True):
+    import torch
+    mask = None
+    if layer_mask is not None:
+        mask = (C.c_uint8 * len(layer_mask))(*[1 if m else 0 for m in layer_mask])
+    st = lib().vlac_select_static_noalloc(
+        _ptr(frame_prev, torch.uint8, "frame_prev"), _ptr(frame_cur, torch.uint8, "frame_cur"),
+        B, H, W, patch, tau_num, tau_den, top_k, _ptr(attn_mean, torch.float32, "attn_mean"), n_layers,
+        C.cast(mask, C.c_void_p) if mask is not None else None, float(tau_task),
+        _ptr(out_idx, torch.int32, "out_idx"), _ptr(out_order, torch.int32, "out_order"),
+        _ptr(out_count, torch.int32, "out_count"), _ptr(out_relevance, torch.float32, "out_relevance"),
+        stride, _stream(stream))
+    return _ret(st, "vlac_select_static_noalloc", check)
 
 
 def vlac_quantize_e4m3(w, out_codes, out_scales, stream=None, check=True):

@@ -249,6 +249,7 @@ int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out) {
     free(hc); free(hs);
   }
   if (e == hipSuccess) e = (hipError_t)gemm_init();
+  if (e == hipSuccess) e = (hipError_t)select_scratch_init();
   if (e != hipSuccess) {
     const bool oom = (e == hipErrorOutOfMemory);
     free_all(ctx);

@@ -184,6 +184,7 @@ void launch_select(const uint32_t* terms, int B, int L_v, int tau_num, int tau_d
                    const float* attn_mean, int n_layers, const uint8_t* layer_mask_host, int n_rel,
                    uint8_t* flags, float* relevance_ws, int32_t* out_idx, int32_t* out_order,
                    int32_t* out_count, float* out_relevance, int stride, hipStream_t st);
+int select_scratch_init();  // resolves the fixed scratch of vlac_select_static_noalloc on the current device; hipError_t
 void launch_layer_ratio(const float* attn_mean, int n_layers, int B, int L_v, float gain_k,
                         const int32_t* reuse_count, float* out_alpha, int32_t* out_layer_count,
                         hipStream_t st);

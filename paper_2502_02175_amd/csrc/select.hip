@@ -10,6 +10,8 @@
 // All of this is HBM/latency-bound integer work: 2*H*W*3 bytes of pixels per
 // stream are read exactly once, with 16-byte loads over the contiguous run of
 // image rows that one row of patches covers.
+#include <mutex>
+
 #include "common.h"
 
 typedef unsigned __int128 u128;
@@ -300,4 +302,92 @@ void launch_layer_ratio(const float* attn_mean, int n_layers, int B, int L_v, fl
                         hipStream_t st) {
   hipLaunchKernelGGL(layer_ratio_kernel, dim3(B), dim3(256), 0, st, attn_mean, n_layers, B, L_v,
                      gain_k, reuse_count, out_alpha, out_layer_count);
+}
+
+// ---------------------------------------------------------------------------
+// Alg. 1 for callers that cannot allocate: the same three kernels, with their scratch (the
+// patch terms, the score of every patch and the selection flags, which vlac_select_static
+// keeps in its context) in a fixed array in device memory.  Every GPU holds its own copy of
+// the array at its own address; host code only ever uses the address that
+// hipGetSymbolAddress returns for the current device, never the array's name.  Nothing in
+// the array has to start at zero: patch_terms_kernel writes all terms of the call's patches,
+// select_rank_kernel all their scores and flags, before anything reads them.
+// ---------------------------------------------------------------------------
+namespace {
+
+constexpr size_t kNoAllocPatches = VLAC_NOALLOC_MAX_PATCHES;
+constexpr size_t kTermsOff = 0;                                   // uint32 [patches][3]
+constexpr size_t kScoreOff = kTermsOff + kNoAllocPatches * 12;    // float  [patches]
+constexpr size_t kFlagsOff = kScoreOff + kNoAllocPatches * 4;     // uint8  [patches]
+constexpr size_t kScratchBytes = kFlagsOff + kNoAllocPatches;
+
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices];  // per device: where that GPU holds `scratch`
+
+// The address of the current device's copy of the array (looked up once per device).
+hipError_t scratch_of_current_device(unsigned char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = (unsigned char*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+}  // namespace
+
+int select_scratch_init() {
+  unsigned char* p = nullptr;
+  return (int)scratch_of_current_device(&p);
+}
+
+extern "C" int vlac_select_static_noalloc(const uint8_t* frame_prev, const uint8_t* frame_cur, int B, int H,
+                                          int W, int patch, int tau_num, int tau_den, int top_k,
+                                          const float* attn_mean, int n_layers, const uint8_t* layer_mask,
+                                          float tau_task, int32_t* out_idx, int32_t* out_order,
+                                          int32_t* out_count, float* out_relevance, int stride,
+                                          void* stream) {
+  if (!frame_prev || !frame_cur || !out_idx || !out_order || !out_count) return VLAC_E_NULL;
+  if (B < 1 || B > 32767) return VLAC_E_RANGE;
+  if (patch < 1 || patch > 64 || H < 1 || W < 1) return VLAC_E_RANGE;
+  if (H % patch || W % patch) return VLAC_E_SHAPE;
+  const long L_v = (long)(H / patch) * (W / patch);
+  if (L_v > SEL_MAX_LV) return VLAC_E_RANGE;
+  if ((size_t)B * (size_t)L_v > kNoAllocPatches) return VLAC_E_RANGE;  // beyond the fixed scratch
+  if (tau_den < 1 || tau_num < 0 || tau_num > tau_den) return VLAC_E_RANGE;
+  if (top_k < 0 || top_k > L_v) return VLAC_E_RANGE;
+  if (stride < top_k || stride < 1) return VLAC_E_SHAPE;
+  if (tau_task != tau_task) return VLAC_E_RANGE;  // NaN
+  if (attn_mean && (n_layers < 1 || n_layers > 512)) return VLAC_E_RANGE;
+  int n_rel = 0;
+  if (attn_mean) {
+    // the L_v - floor(tau_task * L_v) highest-scoring tokens are task-relevant
+    const double keep = floor((double)tau_task * (double)L_v);
+    const double nr = (double)L_v - keep;
+    n_rel = nr < 0 ? 0 : (nr > (double)L_v ? (int)L_v : (int)nr);
+  }
+  unsigned char* ws = nullptr;
+  if (scratch_of_current_device(&ws) != hipSuccess) {
+    (void)hipGetLastError();
+    return VLAC_E_HIP;
+  }
+  uint32_t* terms = (uint32_t*)(ws + kTermsOff);
+  float* score = (float*)(ws + kScoreOff);
+  uint8_t* flags = (uint8_t*)(ws + kFlagsOff);
+  hipStream_t st = (hipStream_t)stream;
+  launch_patch_terms(frame_prev, frame_cur, B, H, W, patch, terms, st);
+  launch_select(terms, B, (int)L_v, tau_num, tau_den, top_k, attn_mean, attn_mean ? n_layers : 0, layer_mask,
+                n_rel, flags, score, out_idx, out_order, out_count, out_relevance, stride, st);
+  return hipGetLastError() == hipSuccess ? VLAC_OK : VLAC_E_HIP;
 }
