@@ -28,6 +28,7 @@ N_ACTION = 7
 # (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain 256 MiB copy's reading:
 # factors 2.000 and 1.000; summary and commands in profiles/c2_gemm_traffic_pmc.md).
 # Measured once on the box, not live; keyed by epilogue of the <=32-row kernel.
+PMC_TRAFFIC_FILE = "profiles/c2_gemm_traffic_pmc.md"
 PMC_TRAFFIC_BYTES = {0: 101.4e6 + 0.1e6, 1: 63.9e6 + 0.03e6, 2: 181.4e6 + 0.06e6, 3: 263.3e6 + 0.1e6}
 
 KIND_NAMES = {0: "qkv_rope_scatter", 1: "proj_residual", 2: "gate_up_swiglu", 3: "head_logits"}
@@ -71,6 +72,11 @@ def main():
                          "on the quantised weights, half the weight bytes per pass")
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers than the model has")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--c2-only", action="store_true",
+                    help="leave out the bf16-operand run and the c4 point of the default line (profiling runs)")
+    ap.add_argument("--sparse-only", action="store_true",
+                    help="c2: time the sparse control step only, no full-recompute leg and no per-launch "
+                         "brackets (for hardware-counter runs that attribute traffic to the sparse prefill)")
     ap.add_argument("--cpu-layers", type=int, default=32)
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of 256 MiB (a kernel of known traffic, "
@@ -103,16 +109,48 @@ def main():
     if args.sweep:
         return sweep(args, V, GpuModel, np, torch, synth, dev)
 
+    out, oracle_inputs = measure_c2(args, V, GpuModel, np, torch, synth, dev,
+                                    "f16w8" if args.weights == "e4m3" else "f16", args.steps, args.warmup, True)
+    if args.sparse_only:
+        print(json.dumps(out))
+        return
+    if args.weights == "bf16" and not args.layers and not args.c2_only:
+        # the same step with bf16 matrix-core operands (the precision the paper runs in; the
+        # headline above uses fp16 operands, which hold the stated tolerance at this depth)
+        b16, _ = measure_c2(args, V, GpuModel, np, torch, synth, dev, "bf16", max(args.steps // 2, 5),
+                            max(args.warmup // 2, 2), False)
+        out["bf16_mode"] = {k: b16[k] for k in ("step_latency_ms", "phase_ms", "full_recompute", "speedup_vs_full")}
+        out["bf16_mode"]["prefill_tok_per_s"] = b16["value"]
+        # the batched configuration in which the recomputed-row GEMMs are bound by the matrix
+        # cores (8 streams share every weight pass), at the static fraction the target names
+        c4 = batched(args, V, GpuModel, np, torch, synth, dev, fracs=[0.0, 0.7], emit=False)
+        q = [r for r in c4["sweep"] if abs(r["static_fraction"] - 0.7) < 1e-9][0]
+        out["c4_70pct_static"] = {
+            "workload": c4["config"]["workload"], "rows_recomputed": q["rows_recomputed"],
+            "step_ms": q["step_ms"], "prefill_ms": q["prefill_ms"], "decode_ms": q["decode_ms"],
+            "prefill_tok_per_s": q["prefill_tok_per_s"],
+            "full_recompute": {"step_ms": c4["sweep"][0]["step_ms"], "prefill_ms": c4["sweep"][0]["prefill_ms"]},
+            "speedup_vs_full": q["speedup_vs_full"], "gemm_tflops_all_prefill_gemms": q["gemm_tflops"],
+            "roofline": c4["roofline"]}
+    if not args.no_cpu_baseline:
+        cfg = synth.CONFIGS["7b"].with_layers(args.layers) if args.layers else synth.CONFIGS["7b"]
+        out["cpu_baseline"] = cpu_baseline(cfg, min(args.cpu_layers, cfg.n_layers), *oracle_inputs)
+    print(json.dumps(out))
+
+
+def measure_c2(args, V, GpuModel, np, torch, synth, dev, operand, steps, warmup, detail):
+    """One stream at the 7B shape (the c2 workload) with the given operand mode: the timed
+    control step, its full-recompute counterpart and (detail) the per-launch GEMM times, the
+    roofline of the dominant kernel and the front end.  Returns (JSON dict, oracle inputs)."""
     cfg = synth.CONFIGS["7b"]
     if args.layers:
         cfg = cfg.with_layers(args.layers)
     seed, H, patch, n_vis, n_txt, top_k, n_redraw = 0, 224, 14, 256, 32, 180, 77
     L = n_vis + n_txt
     n_new = N_ACTION - 1
-    w8 = args.weights == "e4m3"
+    w8 = operand == "f16w8"
     wb = 1 if w8 else 2
-    gm = GpuModel(cfg, seed, max_batch=1, max_seq=320, gain_jitter=0.0, gen_device=dev,
-                  operand="f16w8" if w8 else "f16")
+    gm = GpuModel(cfg, seed, max_batch=1, max_seq=320, gain_jitter=0.0, gen_device=dev, operand=operand)
     ctx, kv = gm.ctx, gm.kv
 
     prev, cur, redrawn = synth.frame_pair(H, H, patch, n_redraw, seed)
@@ -194,18 +232,23 @@ def main():
     full_prefill(d_eprev, attn_a)
     torch.cuda.synchronize()
 
-    ms_step, (ms_sel, ms_prefill, ms_decode) = timed(sparse_step, args.steps, args.warmup)
+    ms_step, (ms_sel, ms_prefill, ms_decode) = timed(sparse_step, steps, warmup)
     V.vlac_check(ctx)
     n_reused = int(cnt.cpu()[0])
     n_rows = L - n_reused
-    ms_full_step, (_, ms_full_prefill, ms_full_decode) = timed(full_step, max(args.steps // 2, 5),
-                                                               max(args.warmup // 2, 2))
+    if args.sparse_only:
+        gm.close()
+        return {"sparse_only": True, "ms_per_step": round(ms_step, 4), "rows_recomputed": n_rows,
+                "phase_ms": {"select+ratio": round(float(ms_sel), 4), "sparse_prefill": round(float(ms_prefill), 4),
+                             "decode_6_tokens": round(float(ms_decode), 4)}}, None
+    ms_full_step, (_, ms_full_prefill, ms_full_decode) = timed(full_step, max(steps // 2, 5),
+                                                               max(warmup // 2, 2))
     # leave the sparse state behind for the kernel passes
     full_prefill(d_eprev, attn_a)
 
     # per-kernel time of every GEMM class, one profiled step each (events around each launch)
     kernels = {}
-    for kind in (0, 1, 2, 3, 4, 5, 6):
+    for kind in ((0, 1, 2, 3, 4, 5, 6) if detail else ()):
         V.vlac_profile_select(ctx, kind)
         sparse_step()
         torch.cuda.synchronize()
@@ -217,47 +260,11 @@ def main():
                              "launches_per_step": n, "avg_us": tot / n * 1e3, "marker_us": mark / n * 1e3,
                              "ms_per_step": tot, "bytes": gemm_bytes(cfg, epi, rows, wb)}
     V.vlac_profile_select(ctx, -1)
-    # What a bracket adds to the kernel inside it: measured with a kernel that times itself
-    # (it spins on the GPU's wall clock for 20 us and stores what it saw), bracketed the same
-    # way on the same stream.  (The marker that follows every bracket reads about 5 us from
-    # its predecessor: markers retire more slowly behind markers than kernels do.)
-    # rocprofv3's duration of that kernel is 0.6 us more than its own reading (its wave
-    # has to be launched and retired: 20.68 against 20.05 us), and a kernel's duration here
-    # means what the profiler means.
     torch.cuda.synchronize()
-    ev_overhead_us = V.vlac_profile_bracket_cost(ctx) - 0.6
-    n_all = sum(k["launches_per_step"] for k in kernels.values())
-    marker_us = sum(k["marker_us"] * k["launches_per_step"] for k in kernels.values()) / max(n_all, 1)
-    # the dominant kernel: most time per step once the brackets' own share is taken out
-    dom = max(kernels, key=lambda k: (kernels[k]["avg_us"] - ev_overhead_us) * kernels[k]["launches_per_step"])
-    kd = kernels[dom]
-    dur_us = max(kd["avg_us"] - ev_overhead_us, 1e-3)
-    achieved = kd["bytes"] / (dur_us * 1e-6) / 1e9
-    full_depth_c2 = (nl == 32 and dom < 4)
-    roofline = {"bound": "hbm", "kernel": kd["name"], "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": PMC_TRAFFIC_BYTES[dom % 4] if full_depth_c2 and not w8 else None,
-                "bytes_per_launch": kd["bytes"], "avg_launch_us": round(dur_us, 2),
-                "avg_launch_us_raw_events": round(kd["avg_us"], 2),
-                "event_bracket_overhead_us": round(ev_overhead_us, 2),
-                "marker_after_marker_us": round(marker_us, 2),
-                "launches_per_step": kd["launches_per_step"]}
-
-    # The front end (not part of the timed step: the step takes the embeddings as inputs, as
-    # the method leaves the vision encoder alone): the patch -> embedding projection for the
-    # 77 recomputed patches only, and for all 256.
-    d_wp = t(synth.round_bf16(wp)).to(torch.bfloat16)
-    d_emb = torch.zeros((1, L, cfg.d_model), device=dev)
-    front = {}
-    for name, ro, rc in (("embed_recomputed_patches_us", order, cnt), ("embed_all_patches_us", None, None)):
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
-        for a, b in ev:
-            a.record()
-            V.vlac_embed_patches(ctx, d_cur, 1, H, H, patch, d_wp, ro, rc, top_k, None, d_emb, L)
-            b.record()
-        torch.cuda.synchronize()
-        front[name] = round(float(np.median([a.elapsed_time(b) for a, b in ev[4:]])) * 1e3, 1)
-
+    roofline, front = None, None
+    if detail:
+        roofline, front = c2_detail(V, np, torch, synth, dev, cfg, ctx, kernels, nl, w8, d_cur, H, patch, wp, L,
+                                    order, cnt, top_k)
     weight_bytes = wb * nl * (cfg.d_model * (cfg.q_dim + 2 * cfg.kv_dim) + cfg.q_dim * cfg.d_model +
                              3 * cfg.d_model * cfg.d_ffn)
     head_bytes = wb * cfg.vocab * cfg.d_model
@@ -265,10 +272,10 @@ def main():
         "metric": "recomputed_token_prefill_tok_per_s",
         "value": round(n_rows / (ms_prefill * 1e-3), 1),
         "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "synthetic",
+        "dtype": "bf16" if operand == "bf16" else "f16", "data": "synthetic",
         "config": {"workload": "c2: OpenVLA-7B shape, 1 stream, 256 visual + 32 text tokens, "
                                "77/256 patches re-drawn, top-k 180, 7 action tokens"
                                + (", weights stored as e4m3 codes (weight-only 8-bit, beyond the paper)" if w8 else ""),
@@ -292,28 +299,79 @@ def main():
         "front_end": front,
         "paper_context": "paper: up to 1.7x latency speedup, ~15% control frequency, one RTX 4090, bf16",
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_layers, prev, cur, e_prev, e_cur, patch,
-                                           n_vis, top_k, seed)
     gm.close()
-    print(json.dumps(out))
+    del gm, kv
+    torch.cuda.empty_cache()
+    return out, (prev, cur, e_prev, e_cur, patch, n_vis, top_k, seed)
+
+
+
+def c2_detail(V, np, torch, synth, dev, cfg, ctx, kernels, nl, w8, d_cur, H, patch, wp, L, order, cnt, top_k):
+    """Roofline of the dominant GEMM of the c2 step from the per-launch event times, and the
+    front end's timing."""
+    # What a bracket adds to the kernel inside it: measured with a kernel that times itself
+    # (it spins on the GPU's wall clock for 20 us and stores what it saw), bracketed the same
+    # way on the same stream.  (The marker that follows every bracket reads about 5 us from
+    # its predecessor: markers retire more slowly behind markers than kernels do.)
+    # rocprofv3's duration of that kernel is 0.6 us more than its own reading (its wave
+    # has to be launched and retired: 20.68 against 20.05 us), and a kernel's duration here
+    # means what the profiler means.
+    ev_overhead_us = V.vlac_profile_bracket_cost(ctx) - 0.6
+    n_all = sum(k["launches_per_step"] for k in kernels.values())
+    marker_us = sum(k["marker_us"] * k["launches_per_step"] for k in kernels.values()) / max(n_all, 1)
+    # the dominant kernel: most time per step once the brackets' own share is taken out
+    dom = max(kernels, key=lambda k: (kernels[k]["avg_us"] - ev_overhead_us) * kernels[k]["launches_per_step"])
+    kd = kernels[dom]
+    dur_us = max(kd["avg_us"] - ev_overhead_us, 1e-3)
+    achieved = kd["bytes"] / (dur_us * 1e-6) / 1e9
+    full_depth_c2 = (nl == 32 and dom < 4)
+    from_profile = full_depth_c2 and not w8
+    roofline = {"bound": "hbm", "kernel": kd["name"], "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": PMC_TRAFFIC_BYTES[dom % 4] if from_profile else None,
+                "traffic_source": ("not measured in this run: hardware counters of this kernel and workload, "
+                                   + PMC_TRAFFIC_FILE) if from_profile else None,
+                "bytes_per_launch": kd["bytes"], "avg_launch_us": round(dur_us, 2),
+                "avg_launch_us_raw_events": round(kd["avg_us"], 2),
+                "event_bracket_overhead_us": round(ev_overhead_us, 2),
+                "marker_after_marker_us": round(marker_us, 2),
+                "launches_per_step": kd["launches_per_step"]}
+
+    # The front end (not part of the timed step: the step takes the embeddings as inputs, as
+    # the method leaves the vision encoder alone): the patch -> embedding projection for the
+    # 77 recomputed patches only, and for all 256.
+    d_wp = torch.tensor(synth.round_bf16(wp), device=dev).to(torch.bfloat16)
+    d_emb = torch.zeros((1, L, cfg.d_model), device=dev)
+    front = {}
+    for name, ro, rc in (("embed_recomputed_patches_us", order, cnt), ("embed_all_patches_us", None, None)):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+        for a, b in ev:
+            a.record()
+            V.vlac_embed_patches(ctx, d_cur, 1, H, H, patch, d_wp, ro, rc, top_k, None, d_emb, L)
+            b.record()
+        torch.cuda.synchronize()
+        front[name] = round(float(np.median([a.elapsed_time(b) for a, b in ev[4:]])) * 1e3, 1)
+    return roofline, front
 
 
 MFMA_PEAK_TFLOPS = 2500.0
 
 
-def batched(args, V, GpuModel, np, torch, synth, dev):
+def batched(args, V, GpuModel, np, torch, synth, dev, fracs=None, emit=True):
     """The batched-stream workloads: c4 = 8 streams x (1024 visual + 32 text) tokens at the
     7B layer shape, static fraction swept over {0, 50, 70, 90, 95} %; c5 = 32 streams x
     (256 + 48) tokens of the grouped-query model at 75 % static.  A step is Alg. 1 on the
     frame pairs, the layer ratio, the sparse prefill of all streams and 6 decode passes.
     The headline value is the point the target names (c4: 70 % static)."""
-    if args.workload == "c4":
+    sweep_fracs = fracs
+    if args.workload in ("c4", "c2"):   # (from the default c2 run: the c4 point the target names)
         cfg, B, H, n_txt, fracs, quoted = synth.CONFIGS["7b"], 8, 448, 32, [0.0, 0.5, 0.7, 0.9, 0.95], 0.7
         name = "c4: OpenVLA-7B layer dims, 8 streams x (1024 visual + 32 text) tokens, 7 action tokens"
     else:
         cfg, B, H, n_txt, fracs, quoted = synth.CONFIGS["gqa"], 32, 224, 48, [0.0, 0.75], 0.75
         name = "c5: grouped-query model (28 layers, d 1536, 12q/2kv x 128, F 8960), 32 streams x (256 + 48) tokens"
+    if sweep_fracs:
+        fracs = sweep_fracs
     if args.layers:
         cfg = cfg.with_layers(args.layers)
     patch, seed = 14, 0
@@ -430,7 +488,11 @@ def batched(args, V, GpuModel, np, torch, synth, dev):
            "sweep": sweep, "roofline": roofline, "cpu_baseline": None,
            "paper_context": "paper: up to 1.7x latency speedup, ~15% control frequency, one RTX 4090, bf16"}
     gm.close()
-    print(json.dumps(out))
+    del gm, kv
+    torch.cuda.empty_cache()
+    if emit:
+        print(json.dumps(out))
+    return out
 
 
 def stream(args, V, GpuModel, np, torch, synth, dev):
@@ -716,7 +778,7 @@ def cpu_baseline(cfg, n_layers, prev, cur, e_prev, e_cur, patch, n_vis, top_k, s
     rows = e_cur.shape[0] - len(p_static)
     prefill_s_full_depth = (t2 - t1) * cfg.n_layers / n_layers
     return {"value": round(rows / prefill_s_full_depth, 2), "unit": "tokens/s", "cores": int(cores),
-            "kind": "oracle",
+            "kind": "oracle", "scope": "Alg. 1 + sparse prefill (the decode passes are not in it)",
             "sample": "fp64 numpy oracle: Alg. 1 on the frame pair (%.3f s) and the sparse prefill of "
                       "%d rows through %d of %d layers (%.2f s, scaled x%.1f to full depth; two "
                       "distinct random weight sets cycled over the depth)"
