@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libvlac.so")
-SOURCES = ["api.hip", "select.hip", "embed.hip", "rows.hip", "gemm.hip", "gemm_tall.hip", "attn.hip"]
+SOURCES = ["api.hip", "select.hip", "embed.hip", "rows.hip", "gemm.hip", "gemm_tall.hip", "gemm_tall2.hip", "attn.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-I" + os.path.join(ROOT, "include"), "-I" + SRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
