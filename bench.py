@@ -57,7 +57,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c3n", "c4", "c5", "oft"],
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c3n", "c4", "c5", "oft", "select"],
                     help="c2: the benchmark's workload (default); c3: a 64-frame stream with the "
                          "task-relevance filter and layer-adaptive reuse on; c3n: the same on a noisy "
                          "scene with moving distractors at tau = 17/20; c4 / c5: the batched-stream "
@@ -104,6 +104,8 @@ def main():
         return stream(args, V, GpuModel, np, torch, synth, dev)
     if args.workload == "oft":
         return two_views_chunk(args, V, GpuModel, np, torch, synth, dev)
+    if args.workload == "select":
+        return select_only(args, V, np, torch, synth, dev)
     if args.workload != "c2":
         return batched(args, V, GpuModel, np, torch, synth, dev)
     if args.sweep:
@@ -493,6 +495,50 @@ def batched(args, V, GpuModel, np, torch, synth, dev, fracs=None, emit=True):
     if emit:
         print(json.dumps(out))
     return out
+
+
+def select_only(args, V, np, torch, synth, dev):
+    """Alg. 1 alone (frame difference, threshold + top-k, relevance filter) and the layer
+    ratio at the batch sizes of the configurations and at a batch large enough to show
+    bandwidth (2048 streams of 224 x 224 frames: 616 MB of pixels per call): time per call
+    and algorithmic pixel bytes per second (2 H W 3 per stream) against the HBM peak."""
+    nl = 32
+    ccfg = V.ModelCfg(nl, 64, 4, 4, 64, 64, 64, 1e-6, 1e4, 2048, 32, 1)     # selection needs no weights
+    ctx = V.vlac_create(ccfg)
+    rows = []
+    for name, B, H, k in (("c2: 1 stream, 224 x 224", 1, 224, 180), ("c5: 32 streams, 224 x 224", 32, 224, 256),
+                          ("c4: 8 streams, 448 x 448", 8, 448, 1024), ("2048 streams, 224 x 224", 2048, 224, 180)):
+        L_v = (H // 14) ** 2
+        g = torch.Generator(device=dev)
+        g.manual_seed(B)
+        prev = torch.randint(0, 256, (B, H, H, 3), dtype=torch.uint8, device=dev, generator=g)
+        cur = (prev.to(torch.int16) + torch.randint(-2, 3, prev.shape, device=dev, generator=g).to(torch.int16)
+               ).clamp_(0, 255).to(torch.uint8)
+        attn = torch.rand((nl, B, L_v), device=dev, generator=g)
+        idx = torch.zeros((B, k), dtype=torch.int32, device=dev)
+        order = torch.zeros((B, k), dtype=torch.int32, device=dev)
+        cnt = torch.zeros(B, dtype=torch.int32, device=dev)
+        alpha = torch.zeros((B, nl), device=dev)
+        lcount = torch.zeros((B, nl), dtype=torch.int32, device=dev)
+        reps = 30
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(reps)]
+        for e in ev:
+            e[0].record()
+            V.vlac_select_static(ctx, prev, cur, B, H, H, 14, 249, 250, k, attn, None, 0.5, idx, order, cnt, None, k)
+            e[1].record()
+            V.vlac_layer_ratio(ctx, attn, B, L_v, 1.0, cnt, alpha, lcount)
+            e[2].record()
+        torch.cuda.synchronize()
+        sel = float(np.median([e[0].elapsed_time(e[1]) for e in ev[5:]]))
+        rat = float(np.median([e[1].elapsed_time(e[2]) for e in ev[5:]]))
+        pix = 2 * B * H * H * 3
+        rows.append({"workload": name, "select_static_us": round(sel * 1e3, 1), "layer_ratio_us": round(rat * 1e3, 1),
+                     "pixel_bytes": pix, "pixel_GBps_over_select_call": round(pix / (sel * 1e-3) / 1e9, 1),
+                     "frac_of_hbm_peak": round(pix / (sel * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
+        del prev, cur, attn
+    V.vlac_destroy(ctx)
+    print(json.dumps({"metric": "alg1_selection_time", "n_gpus": 1, "data": "synthetic", "dtype": "u8",
+                      "config": {"workload": "Alg. 1 + layer ratio alone"}, "rows": rows}))
 
 
 def stream(args, V, GpuModel, np, torch, synth, dev):
