@@ -34,8 +34,24 @@ class LayerW(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("wqkv", "wo", "w_gate_up", "w_down", "g_attn", "g_ffn")]
 
 
+_PATH = os.path.join(_HERE, "libvlac.so")
+_LOADED = {}
+
+
 def lib_path():
-    return os.path.join(_HERE, "libvlac.so")
+    return _PATH
+
+
+def use_library(path=None):
+    """Switches every later call of this binding to another build of the library (None: the
+    product build, libvlac.so).  For the test that compares libvlac_safe.so, the build whose
+    hand-placed waits are replaced by full waits, with the product build.  A context belongs
+    to the library that created it: destroy it before switching."""
+    global _LIB, _PATH
+    if _LIB is not None:
+        _LOADED[_PATH] = _LIB
+    _PATH = path or os.path.join(_HERE, "libvlac.so")
+    _LIB = _LOADED.get(_PATH)
 
 
 def lib():

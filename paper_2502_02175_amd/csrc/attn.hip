@@ -403,10 +403,10 @@ __global__ __launch_bounds__(256, 3) void attn_rows4_kernel(AttnArgs a) {
     // wave has left tile kt - 1, whose buffer takes tile kt + AHEAD
     constexpr int YOUNGER = 2 * PER * (AHEAD - 1);
     static_assert(YOUNGER == 0 || YOUNGER == 2 || YOUNGER == 4 || YOUNGER == 8, "add the wait for this count");
-    if (YOUNGER == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else if (YOUNGER == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    else if (YOUNGER == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (YOUNGER == 8) VLAC_VMCNT(8);
+    else if (YOUNGER == 4) VLAC_VMCNT(4);
+    else if (YOUNGER == 2) VLAC_VMCNT(2);
+    else VLAC_VMCNT(0);
     __syncthreads();
     copy_tile(min(kt + AHEAD, n_kt_wg - 1), (kt + AHEAD) % NBUF);
     if (kt < n_kt) {

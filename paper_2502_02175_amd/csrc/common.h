@@ -85,6 +85,17 @@ __device__ inline f32x16 mfma32(const uint4& a, const uint4& b, const f32x16& c)
 }
 #endif
 
+// Hand-placed waits for copies that the compiler does not see (global -> LDS copies written
+// as inline assembly): "at most n vector-memory operations outstanding".  A build with
+// -DVLAC_SAFE_WAITS waits for all of them instead; it computes the same values in the same
+// order, so its results must equal the normal build's bit for bit, and a miscounted wait (an
+// LDS read before its tile has landed) shows as a difference between the two builds.
+#ifdef VLAC_SAFE_WAITS
+#define VLAC_VMCNT(n) asm volatile("s_waitcnt vmcnt(0)" ::: "memory")
+#else
+#define VLAC_VMCNT(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
+#endif
+
 enum { VLAC_ERR_BAD_INDEX = 1 };  // bits of the device-side error word
 
 struct LayerW {

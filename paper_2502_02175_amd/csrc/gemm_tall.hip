@@ -120,9 +120,9 @@ __device__ __forceinline__ void tall_body(const GemmArgs& a, uint4* lds, int til
   // compiler drops them.  There the wait is for everything.)
 #define VLAC_TALL_STEP(i, ph, s0, s1, s2, s3, ALL)           \
   {                                                          \
-    if (ALL) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                  \
-    else if (NF == 2) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");        \
-    else asm volatile("s_waitcnt vmcnt(10)" ::: "memory");                     \
+    if (ALL) VLAC_VMCNT(0);                                  \
+    else if (NF == 2) VLAC_VMCNT(18);                        \
+    else VLAC_VMCNT(10);                                     \
     __syncthreads();                                         \
     copy_x((i) + 2, ((ph) + 2) % 3);                         \
     ktile((i), 0, ph, W[s0]);                                \
@@ -136,8 +136,8 @@ __device__ __forceinline__ void tall_body(const GemmArgs& a, uint4* lds, int til
 #pragma unroll
   for (int kt = 0; kt < 6; ++kt) load_w(kt, W[kt]);
   // both copies; the 6 NF weight loads fly on
-  if (NF == 2) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+  if (NF == 2) VLAC_VMCNT(12);
+  else VLAC_VMCNT(6);
   int i = 0;
   for (; i + 3 <= KS; i += 3) {
     VLAC_TALL_STEP(i, 0, 0, 1, 2, 3, false)

@@ -24,12 +24,6 @@
 //    from the row count).
 #include "gemm_epi.h"
 
-#ifdef VLAC_SAFE_WAITS
-#define VLAC_VMCNT(n) asm volatile("s_waitcnt vmcnt(0)" ::: "memory")
-#else
-#define VLAC_VMCNT(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
-#endif
-
 namespace {
 
 #ifndef VLAC_T2_RING

@@ -252,7 +252,9 @@ def test_gqa_32_streams_properties():
         more = [sorted(set(reuse[b]) | set(np.flatnonzero(changed[b])[:13].tolist())) for b in range(B)]
         same2 = gm.prefill(e0, n_vis, more, want_hidden=False)     # 25 row blocks against 28: same K split
         np.testing.assert_array_equal(same2["logits"], same["logits"])
-        np.testing.assert_allclose(same["logits"], full["logits"], atol=5e-2)
+        # (both sides are within 5e-3 of the oracle at this depth, tests/test_gpu_depth.py: the
+        # oracle's own bar holds between them)
+        np.testing.assert_allclose(same["logits"], full["logits"], atol=2e-2)
         np.testing.assert_allclose(same["attn_mean"], full["attn_mean"], rtol=1e-2, atol=1e-6)
         t_same, _ = gm.decode(B, n_vis + n_txt, 6, same["token"])
         t_same2, _ = gm.decode(B, n_vis + n_txt, 6, same2["token"])
