@@ -114,13 +114,13 @@ size_t vlac_kv_cache_bytes(const vlac_model_cfg* cfg);
 /* How a projection of a batched prefill (Alg. 2 over the rows of many streams: the
  * many-rows GEMM) cuts its work for a given row count; the kernels decide this on the
  * device, this is the same rule for inspection and tests.  out_features x k is the weight
- * matrix, rows the recomputed rows of the launch, max_splits the most K splits the
+ * matrix, rows the recomputed rows of the launch, max_splits the most K parts the
  * projection may use (1 unless it adds to the residual stream; at most 3).
- * Results: features per work item (512 or 256), K splits, work items
- * (weight tiles x splits x blocks of 128 rows).  Needs neither a context nor a GPU.
+ * Results: rows per work item (256, 192 or 128; a work item is 256 features wide), K parts,
+ * work items (weight tiles x parts x row blocks).  Needs neither a context nor a GPU.
  * VLAC_E_NULL / VLAC_E_RANGE on null pointers or non-positive sizes. */
 int vlac_plan_many_rows_gemm(int out_features, int k, int rows, int max_splits,
-                             int* tile_features, int* k_splits, int* work_items);
+                             int* block_rows, int* k_splits, int* work_items);
 
 /* Zero-fills stream b's part of the cache and marks it "never filled": the next
  * prefill of that stream must be a full one.  Must be called once per stream

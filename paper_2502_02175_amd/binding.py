@@ -144,7 +144,7 @@ def _cfg(cfg, max_batch=None, max_seq=None):
 
 
 def vlac_plan_many_rows_gemm(out_features, k, rows, max_splits=1):
-    """-> (features per work item, K splits, work items); no GPU needed."""
+    """-> (rows per work item, K parts, work items); no GPU needed."""
     tf, ks, wi = C.c_int(), C.c_int(), C.c_int()
     st = lib().vlac_plan_many_rows_gemm(out_features, k, rows, max_splits, C.byref(tf), C.byref(ks), C.byref(wi))
     if st != 0:

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libvlac.so")
-SOURCES = ["api.hip", "select.hip", "embed.hip", "rows.hip", "gemm.hip", "gemm_tall.hip", "gemm_tall2.hip", "attn.hip"]
+SOURCES = ["api.hip", "select.hip", "embed.hip", "rows.hip", "gemm.hip", "gemm_tall.hip", "attn.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-I" + os.path.join(ROOT, "include"), "-I" + SRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -26,7 +26,7 @@ def _run(cmd):
 # The sources that place waits for compiler-invisible copies by hand; libvlac_safe.so is the
 # same library with those sources compiled with -DVLAC_SAFE_WAITS (every such wait is for all
 # outstanding loads): a checking aid that a GPU test compares with libvlac.so bit for bit.
-HAND_WAITS = ["gemm_tall.hip", "gemm_tall2.hip", "attn.hip"]
+HAND_WAITS = ["gemm_tall.hip", "attn.hip"]
 LIB_SAFE = os.path.join(HERE, "libvlac_safe.so")
 
 

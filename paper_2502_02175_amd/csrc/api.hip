@@ -94,14 +94,13 @@ const char* vlac_status_string(int s) {
 }
 
 int vlac_plan_many_rows_gemm(int out_features, int k, int rows, int max_splits,
-                             int* tile_features, int* k_splits, int* work_items) {
-  if (!tile_features || !k_splits || !work_items) return VLAC_E_NULL;
+                             int* block_rows, int* k_splits, int* work_items) {
+  if (!block_rows || !k_splits || !work_items) return VLAC_E_NULL;
   if (out_features < 1 || k < 1 || rows < 1 || max_splits < 1) return VLAC_E_RANGE;
-  const int row_blocks = (rows + 127) / 128;
-  const TallPlan pl = tall_plan((out_features + 31) / 32, row_blocks, round_up(k, 64) / 64, max_splits);
-  *tile_features = 256 * pl.nf;
+  const TallPlan pl = tall_plan(((out_features + 31) / 32 + 7) / 8, rows, max_splits, round_up(k, 64) / 64);
+  *block_rows = 64 * pl.rt;
   *k_splits = pl.S;
-  *work_items = pl.tiles * pl.S * row_blocks;
+  *work_items = pl.items();
   return VLAC_OK;
 }
 

@@ -109,7 +109,7 @@ struct LayerW {
 struct SplitAdapt {
   const int* n_rows;  // device: the row count the GEMM ran with (n_rows_host >= 0: not read)
   int n_rows_host, n_blocks, KS;  // the GEMM's feature blocks and 64-k steps
-  int S_tall;         // most splits the many-rows kernel may have used
+  int S_tall;         // most splits the many-rows kernel may have used (tall_plan)
   int small_below;    // > 0: with fewer rows than this the one-stream kernel ran instead ...
   int S_small;        // ... and split K in this many parts (1: it completed the rows itself)
 };
@@ -265,54 +265,51 @@ struct NormIn {
   float* dst;          // where the completed rows are stored (never src), or null
   size_t dst_stride;
 };
-// The many-rows GEMM decides on the device, from the ACTUAL row count, how it cuts its work
-// where weight tiles of 512 features x row blocks of 128 rows give less than one work item
-// per CU: weight tiles of 256 features (one feature block per wave instead of two), and,
-// with a residual epilogue, K split in up to S_max parts whose partial rows the row kernel
-// that follows adds up (S = 1: not split, the GEMM adds to the residual stream itself).
-// Both that kernel and the row kernel that consumes the partial rows call this function.
-struct TallPlan { int nf, tiles, S; };
-__host__ __device__ inline TallPlan tall_plan(int n_blocks, int row_blocks, int KS, int S_max) {
-  TallPlan best;
-  best.nf = 2;
-  best.tiles = (n_blocks + 15) >> 4;
-  best.S = 1;
-  const int items2 = best.tiles * row_blocks;
-  if (items2 > 256) {
-    // More than one round of 256 items: the narrow tiles only where they save most of a round
-    // (a little more than one round of wide items takes two: 301 items of cost 1 against
-    // 602 of cost 0.575 in three rounds), with a margin, because short items of ragged row
-    // blocks fill gaps that this count of rounds does not see.
-    const int tiles1 = (n_blocks + 7) >> 3;
-    const int cost_w = ((items2 + 255) >> 8) * 200, cost_n = ((tiles1 * row_blocks + 255) >> 8) * 115;
-    if (cost_n * 11 < cost_w * 10) {
-      best.nf = 1;
-      best.tiles = tiles1;
-    }
-    return best;
-  }
-  if (items2 > 128 || items2 < 1) return best;  // no other cut fits into one round of 256 items
-  // Less than one work item per two CUs: of the cuts that still give at most 256 items, take
-  // the one with the least estimated item time (in integers, so that host and device agree):
-  // an item of the narrow tile costs 0.575 of a wide one (half the MFMAs, 1.15 times the
-  // operand bytes per MFMA), a split divides K and adds 8 % per extra part for the partial rows.
-  if (S_max < 1 || KS < 64) S_max = 1;
+// The many-rows kernel with both operands through LDS (gemm_tall.hip) cuts the rows of a
+// launch into blocks of 256, 192 or 128 rows (a work item is 256 features wide and fetches 16,
+// 14 or 12 KiB of operands per k-tile for 64, 48 or 32 MFMAs) and, where the projection adds
+// to the residual stream, K into up to S_max parts whose partial rows the row kernel that
+// follows adds up; the cut follows from the ACTUAL row count, on the device.  Taken is the cut
+// with the least estimated time: rounds of 256 work items x the KiB an item moves (its
+// operands over its share of K; with K split also its partial rows, written once and read once
+// by the row kernel: 2 x 64 rt rows x 256 features x 4 bytes, counted twice, because they go
+// through memory where operand tiles are mostly shared in L2); ties go to the larger block
+// and the fewer parts.  KS: 64-k steps of the projection.  Both the GEMM and the row kernel
+// that consumes the partial rows call this function (32-bit arithmetic, divisions by
+// constants only).
+struct TallPlan {
+  int rt, tiles, row_blocks, S;  // row tiles per wave (4, 3 or 2), weight tiles of 256 features, row blocks, K parts
+  __host__ __device__ int items() const { return tiles * S * row_blocks; }
+};
+__host__ __device__ inline TallPlan tall_plan(int tiles, int n_rows, int S_max, int KS) {
+  TallPlan p;
+  p.tiles = tiles;
+  p.rt = 4;
+  p.S = 1;
+  p.row_blocks = (n_rows + 255) >> 8;
   if (S_max > 3) S_max = 3;
-  int best_cost = 0x7fffffff;
-  for (int nf = 2; nf >= 1; --nf) {
-    const int tiles = nf == 2 ? (n_blocks + 15) >> 4 : (n_blocks + 7) >> 3;
-    for (int S = 1; S <= S_max; ++S) {
-      if (tiles * S * row_blocks > 256) continue;
-      const int cost = (nf == 2 ? 200 : 115) * (6 / S) * (100 + 8 * (S - 1));
-      if (cost < best_cost) {
-        best_cost = cost;
-        best.nf = nf;
-        best.tiles = tiles;
-        best.S = S;
-      }
-    }
+  if (S_max < 1 || KS < 24) S_max = 1;
+  if (KS > 8192) KS = 8192;  // (keeps the estimate inside 32 bits; the choice no longer depends on K there)
+  unsigned best = 0xffffffffu;
+#define VLAC_TALL_TRY(S_, RT_)                                                                     \
+  if (S_ <= S_max) {                                                                             \
+    const unsigned rb = ((unsigned)n_rows + 64u * RT_ - 1u) / (64u * RT_);                       \
+    unsigned rounds = ((unsigned)tiles * S_ * rb + 255u) >> 8;                                   \
+    if (rounds > 4096u) rounds = 4096u;                                                          \
+    const unsigned steps = (2u * (unsigned)KS + S_ - 1u) / S_;                                   \
+    const unsigned cost = rounds * (2u * (8u + 2u * RT_) * steps + (S_ > 1 ? 256u * RT_ : 0u));  \
+    if (cost < best) {                                                                           \
+      best = cost;                                                                               \
+      p.rt = RT_;                                                                                \
+      p.row_blocks = (int)rb;                                                                    \
+      p.S = S_;                                                                                  \
+    }                                                                                            \
   }
-  return best;
+  VLAC_TALL_TRY(1, 4) VLAC_TALL_TRY(1, 3) VLAC_TALL_TRY(1, 2)
+  VLAC_TALL_TRY(2, 4) VLAC_TALL_TRY(2, 3) VLAC_TALL_TRY(2, 2)
+  VLAC_TALL_TRY(3, 4) VLAC_TALL_TRY(3, 3) VLAC_TALL_TRY(3, 2)
+#undef VLAC_TALL_TRY
+  return p;
 }
 // the same for the GEMM that launch_gemm(EPI_RESID, ...) with these arguments launches
 SplitAdapt gemm_resid_adapt(vlac_ctx* c, int n_blocks, int kpad, int rows_cap, const int* n_rows, int n_rows_host);

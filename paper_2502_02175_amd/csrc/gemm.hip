@@ -28,7 +28,6 @@
 //    is sized for the worst case and surplus workgroups leave at once.
 //  * Workgroup ids are dealt round-robin to the 8 XCDs; row blocks of one weight
 //    tile are mapped to the same XCD so that they share its L2.
-#include <cstdlib>
 #include <cstring>
 #include "gemm_epi.h"
 
@@ -534,7 +533,7 @@ int gemm_init() {
   if ((e = set_attr<MT, EPI_LOGITS>()) != hipSuccess) return (int)e;
   VLAC_SET(4)
 #undef VLAC_SET
-  return gemm_tall2_init();
+  return gemm_tall_init();
 }
 
 template <int MT, bool F16, bool W8>
@@ -593,7 +592,6 @@ bool gemm_can_fuse_norm(int n_rows_host, int decode_pos, int kpad) {
 // the matrix is expanded to fp16 before every launch, 3 bytes of traffic per weight
 // against the 2 rows flops per weight that such a launch spends on it.)
 static const int kTallRows = 512;
-static const bool kTall2Off = getenv("VLAC_TALL2_OFF") != nullptr;  // measurement aid: the first many-rows kernel for every projection
 static bool use_tall(const vlac_ctx* c, int rows_cap) {
   return rows_cap >= kTallRows && (!c->w8 || (rows_cap >= 1024 && c->wdeq));
 }
@@ -742,10 +740,8 @@ int launch_gemm(vlac_ctx* c, int epi, const bf16_t* wp, const float* wscale, int
       launch_expand_e4m3(a.wp, (uint4*)c->wdeq, (size_t)n_blocks * 2 * a.KS, st);
       a.wp = (const uint4*)c->wdeq;
     }
-    // the projections with a residual may split K and leave partial rows to the next row kernel
-    // (gemm_tall.hip); the others complete their sums in the kernel with both operands in LDS
-    if (epi == EPI_RESID || kTall2Off) launch_gemm_tall(c->f16, epi, a, rows_cap, tall_resid_smax(c, epi, rows_cap, e.d_model), st);
-    else launch_gemm_tall2(c->f16, epi, a, rows_cap, st);
+    // (the projections with a residual may split K and leave partial rows to the next row kernel)
+    launch_gemm_tall(c->f16, epi, a, rows_cap, tall_resid_smax(c, epi, rows_cap, e.d_model), st);
     if (S_small > a.S) a.S = S_small;  // (the caller learns the most splits either kernel may leave)
   } else {
     launch_rows_kernel(c, epi, a, rows_cap, e, st);

@@ -14,7 +14,7 @@ struct GemmArgs {
   int n_rows_val;     // >= 0: the row count is known on the host, n_rows is not read
   int rows_lo, rows_hi;  // the launch has work only if rows_lo <= row count < rows_hi (two kernels share a GEMM)
   int S, MB, P;       // split-K factor, row blocks, weight tiles * S
-  int x_tiles;        // gemm_tall2: 32-row tiles the activation buffer holds (copies are clamped to it)
+  int x_tiles;        // many-rows GEMM: 32-row tiles the activation buffer holds (copies are clamped to it)
   float* partial;
   int* counters;
   GemmEpi e;
@@ -133,36 +133,10 @@ __device__ inline void epilogue_tile(const GemmEpi& e, int nb, int slot, int id,
   }
 }
 
-// gemm_tall.hip: the kernel for many rows (matrix-core bound).  The caller has filled
-// every field of `a` except S, MB and P.
+// gemm_tall.hip: the many-rows kernel with both operands through LDS (its plan: common.h).
+// The caller has filled every field of `a` except S, MB, P and x_tiles; S_max: most K splits
+// (1 unless the projection adds to the residual stream).
 void launch_gemm_tall(bool f16, int epi, GemmArgs& a, int rows_cap, int S_max, hipStream_t st);
-// gemm_tall2.hip: the many-rows kernel with both operands through LDS, for the projections
-// that complete their sums inside the kernel (QKV, gate/up).  How it cuts the rows of a
-// launch into blocks follows from the ACTUAL row count, on the device: blocks of 256, 192 or
-// 128 rows (a work item is 256 features wide and fetches 16, 14 or 12 KiB of operands per
-// k-tile for 64, 48 or 32 MFMAs); the cut that takes the least time by this estimate: rounds
-// of 256 work items x the operand bytes of an item.  Ties go to the larger block.
-struct Tall2Plan {
-  int rt, tiles, row_blocks;  // row tiles per wave (4, 3 or 2), weight tiles of 256 features, row blocks
-  __host__ __device__ int items() const { return tiles * row_blocks; }
-};
-__host__ __device__ inline Tall2Plan tall2_plan(int tiles, int n_rows) {
-  Tall2Plan p;
-  p.tiles = tiles;
-  p.rt = 4;
-  int best = 0x7fffffff;
-  for (int rt = 4; rt >= 2; --rt) {
-    const int rb = (n_rows + 64 * rt - 1) / (64 * rt);
-    const int cost = ((tiles * rb + 255) >> 8) * (8 + 2 * rt);
-    if (cost < best) {
-      best = cost;
-      p.rt = rt;
-      p.row_blocks = rb;
-    }
-  }
-  return p;
-}
-void launch_gemm_tall2(bool f16, int epi, GemmArgs& a, int rows_cap, hipStream_t st);
-int gemm_tall2_init();  // kernel attribute setup; returns hipError_t
+int gemm_tall_init();  // kernel attribute setup; returns hipError_t
 // e4m3 weight codes (n_slots slots of two k-tiles, 64 uint4 each) -> fp16 tiles, fragment order
 void launch_expand_e4m3(const uint4* codes, uint4* tiles, size_t n_slots, hipStream_t st);

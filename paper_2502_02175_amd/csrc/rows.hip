@@ -291,7 +291,7 @@ __global__ __launch_bounds__(256) void resid_norm_rows_kernel(
     // the GEMM chose its split factor from its row count; unsplit, it added to the
     // residual stream itself and left no partial rows
     const int n_g = adapt.n_rows_host >= 0 ? adapt.n_rows_host : *adapt.n_rows;
-    S = n_g < adapt.small_below ? adapt.S_small : tall_plan(adapt.n_blocks, (n_g + 127) >> 7, adapt.KS, adapt.S_tall).S;
+    S = n_g < adapt.small_below ? adapt.S_small : tall_plan((adapt.n_blocks + 7) >> 3, n_g, adapt.S_tall, adapt.KS).S;
     if (S == 1) {
       S = 0;
       r = y;

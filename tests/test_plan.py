@@ -1,5 +1,10 @@
 """Host logic without a GPU: how the many-rows GEMM cuts its work (the rule the kernels
-evaluate on the device, through its inspection entry point)."""
+evaluate on the device, through its inspection entry point).  The expected values are worked
+out by hand from the rule as the header states it: a work item is 256 features wide and 256,
+192 or 128 rows tall and moves 2 x (8 + 2 rt) KiB of operands per 32-k step (rt = rows / 64);
+with K in S > 1 parts it also moves 256 rt KiB for its partial rows (64 rt rows x 256 features
+x 4 bytes, written once, read once, counted twice); the estimate is rounds of 256 items x the
+KiB of an item; ties go to the taller item and the fewer parts."""
 import ctypes as C
 
 import pytest
@@ -9,49 +14,49 @@ import paper_2502_02175_amd as V
 PLAN = V.vlac_plan_many_rows_gemm
 
 
-def test_large_launches_keep_the_wide_unsplit_tile():
-    # 7B gate/up at 2712 rows: 43 wide tiles x 22 row blocks, several rounds of 256 items
-    assert PLAN(2 * 11008, 4096, 2712, 1) == (512, 1, 43 * 22)
-    # 4096-wide projection at 8448 rows, residual epilogue: no split either
-    assert PLAN(4096, 11008, 8448, 3) == (512, 1, 8 * 66)
+def test_large_launches_are_not_split():
+    # 7B gate/up at 2712 rows: 86 tiles; 256-row items: 11 blocks, 946 items, 4 rounds x 4096 KiB;
+    # 192-row: 15 blocks, 1290 items, 6 rounds x 3584; 128-row: 22 blocks, 8 rounds x 3072
+    assert PLAN(2 * 11008, 4096, 2712, 1) == (256, 1, 946)
+    # 7B QKV at 2712 rows: 48 tiles; 528 items of 256 rows take 3 rounds x 4096, 720 items of 192
+    # rows 3 rounds x 3584, 1056 items of 128 rows 5 rounds x 3072
+    assert PLAN(12288, 4096, 2712, 1) == (192, 1, 720)
+    # 4096-wide projection with K 11008 (344 steps) at 8448 rows, residual epilogue: 704 items of
+    # 192 rows in 3 rounds x 9632 KiB; two parts would take 5 rounds x 6528
+    assert PLAN(4096, 11008, 8448, 3) == (192, 1, 704)
 
 
-def test_few_items_are_cut_finer_but_fit_one_round():
-    # d_model 1536 (3 wide tiles), K 8960, 3584 rows (28 blocks): 84 items -> 3 K splits of the wide tile
-    assert PLAN(1536, 8960, 3584, 3) == (512, 3, 252)
-    # the same without a residual epilogue: narrow tiles only
-    assert PLAN(1536, 8960, 3584, 1) == (256, 1, 168)
-    # 4096-wide projection at 664 rows (6 blocks): 48 items -> narrow tiles in 2 splits
-    assert PLAN(4096, 4096, 664, 3) == (256, 2, 192)
-    # short K carries no split
-    assert PLAN(1536, 1536, 3584, 3) == (256, 1, 168)
-
-
-def test_a_little_more_than_a_round_takes_the_narrow_tile():
-    # 8 wide tiles x 34 row blocks = 272 items (two rounds) -> 544 narrow ones (three shorter rounds)
-    assert PLAN(4096, 4096, 4352, 3) == (256, 1, 544)
-    # 24 wide tiles x 22 blocks = 528 items: three rounds either way, stays wide
-    assert PLAN(12288, 4096, 2712, 1) == (512, 1, 528)
+def test_few_items_are_cut_finer():
+    # d_model 1536 (6 tiles), K 8960 (280 steps), 3584 rows: 84 items of 256 rows leave two
+    # thirds of the CUs idle; 3 parts of 94 steps: 252 items x (3008 + 1024) KiB in one round
+    assert PLAN(1536, 8960, 3584, 3) == (256, 3, 252)
+    # the same without a residual epilogue: the shortest items (168 x 6720 KiB, one round)
+    assert PLAN(1536, 8960, 3584, 1) == (128, 1, 168)
+    # K 1536 (48 steps): the partial rows of a split would outweigh the operands
+    assert PLAN(1536, 1536, 3584, 3) == (128, 1, 168)
+    # 4096-wide projection, K 4096 (128 steps), 664 rows: 3 parts x 4 blocks of 192 rows x 16 tiles
+    # = 192 items x (1204 + 768) KiB against 96 unsplit items of 128 rows x 3072 KiB
+    assert PLAN(4096, 4096, 664, 3) == (192, 3, 192)
+    # K below 1536 carries no split at all
+    assert PLAN(1536, 1024, 3584, 3) == (128, 1, 168)
 
 
 @pytest.mark.parametrize("n", [1536, 2048, 4096, 12288, 17920, 22016])
-@pytest.mark.parametrize("k", [1536, 4096, 8960, 11008])
+@pytest.mark.parametrize("k", [1024, 1536, 4096, 8960, 11008])
 @pytest.mark.parametrize("smax", [1, 3])
 def test_invariants_over_row_counts(n, k, smax):
-    prev_items_per_block = None
+    tiles = -(-n // 256)
     for rows in list(range(1, 700, 37)) + list(range(700, 9000, 411)):
-        tile, s, items = PLAN(n, k, rows, smax)
-        blocks = (rows + 127) // 128
-        tiles = -(-n // tile)
-        assert tile in (256, 512) and 1 <= s <= smax
-        assert items == tiles * s * blocks
+        block, s, items = PLAN(n, k, rows, smax)
+        assert block in (128, 192, 256) and 1 <= s <= smax
+        assert items == tiles * s * -(-rows // block)
         if s > 1:
-            assert k >= 4096 and items <= 256          # splits only for long K, and only within one round
-        wide_items = -(-n // 512) * blocks
-        if wide_items > 128 and wide_items <= 256:
-            assert (tile, s) == (512, 1)                # no finer cut fits one round
-        if tile == 256 and wide_items <= 256:
-            assert items <= 256
+            assert k >= 1536
+        # never more rounds of 256 items than the plainest cut (256-row items, unsplit) would take
+        # at a higher cost per item: the chosen estimate is the least of the nine
+        steps = lambda S: -(-2 * (-(-k // 64)) // S)
+        cost = lambda b, S: -(-(tiles * S * -(-rows // b)) // 256) * (2 * (8 + b // 32) * steps(S) + (4 * b if S > 1 else 0))
+        assert cost(block, s) == min(cost(b, S) for b in (128, 192, 256) for S in range(1, (smax if k >= 1536 else 1) + 1))
 
 
 def test_bad_arguments():
