@@ -83,17 +83,21 @@ __device__ __forceinline__ int tall_body(const GemmArgs& a, uint4* lds, TallItem
   // activation tiles of row tiles 2w, 2w + 1 of the block (both k-tiles of each: 2 KiB that
   // lie together in global memory and in LDS).  Row blocks of 128 rows have 4 row tiles:
   // waves 2 and 3 copy tiles 4..7 all the same (clamped, unread).
-  const uint4 *src[4], *srcn[4];
+  // (scalar base addresses: a copy is then one scalar select, one scalar add and the load, with
+  // the lane's 16-byte offset in one register for all of them; a wave has one instruction stream,
+  // and what a copy costs to issue is taken from its MFMAs)
+  const char *src[4], *srcn[4];
   uint32_t dst[4];
   const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds);
+  const uint32_t lane_off = (uint32_t)lane * 16u;
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
     const int fb = 2 * w + p;
-    src[p] = a.wp + ((size_t)min(nb0 + fb, a.NB - 1) * KC + 2 * step0) * 64 + lane;
-    srcn[p] = a.wp + ((size_t)min(nx.tile * 8 + fb, a.NB - 1) * KC + 2 * step0n) * 64 + lane;
+    src[p] = (const char*)(a.wp + ((size_t)min(nb0 + fb, a.NB - 1) * KC + 2 * step0) * 64);
+    srcn[p] = (const char*)(a.wp + ((size_t)min(nx.tile * 8 + fb, a.NB - 1) * KC + 2 * step0n) * 64);
     dst[p] = lds0 + (uint32_t)(fb * 2) * 1024u;
-    src[2 + p] = a.xp + ((size_t)min((row0 >> 5) + fb, a.x_tiles - 1) * KC + 2 * step0) * 64 + lane;
-    srcn[2 + p] = a.xp + ((size_t)min(nx.mb * (2 * RT) + fb, a.x_tiles - 1) * KC + 2 * step0n) * 64 + lane;
+    src[2 + p] = (const char*)(a.xp + ((size_t)min((row0 >> 5) + fb, a.x_tiles - 1) * KC + 2 * step0) * 64);
+    srcn[2 + p] = (const char*)(a.xp + ((size_t)min(nx.mb * (2 * RT) + fb, a.x_tiles - 1) * KC + 2 * step0n) * 64);
     dst[2 + p] = lds0 + 16384u + (uint32_t)(fb * 2) * 1024u;
   }
   // one eighth (j) of this wave's copies of stage i: k-tile j % 2 of operand tile row j / 2.
@@ -101,15 +105,15 @@ __device__ __forceinline__ int tall_body(const GemmArgs& a, uint4* lds, TallItem
   // (never read): the number of copies per step is the same at every step.
   auto copy_one = [&](int i, int slot_, int j) {
     const bool mine = i < n_steps || !chain;
-    const size_t k = (size_t)(mine ? min(i, n_steps - 1) : min(i - n_steps, n_steps_n - 1)) * 128;  // 2 k-tiles of 64 uint4
-    const uint4* sp = (mine ? src[j >> 1] : srcn[j >> 1]) + k + (j & 1) * 64;
+    const size_t k = (size_t)(mine ? min(i, n_steps - 1) : min(i - n_steps, n_steps_n - 1)) * 2048;  // 2 k-tiles of 1 KiB
+    const char* sp = (mine ? src[j >> 1] : srcn[j >> 1]) + k + (j & 1) * 1024;
     const uint32_t d = dst[j >> 1] + (uint32_t)slot_ * (TALL_STAGE * 16) + (uint32_t)(j & 1) * 1024u;
     asm volatile(
         "s_mov_b32 m0, %0\n\t"
         "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %1, off"
+        "global_load_lds_dwordx4 %1, %2"
         :
-        : "s"(d), "v"(sp)
+        : "s"(d), "v"(lane_off), "s"(sp)
         : "memory", "m0");
   };
 
