@@ -26,10 +26,10 @@ N_ACTION = 7
 
 # HBM bytes per launch of the decode GEMMs at the c2 shape from hardware counters
 # (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain 256 MiB copy's reading:
-# factors 2.000 and 1.000; summary and commands in profiles/c2_gemm_traffic_pmc.md).
+# factors 2.023 and 1.012; summary and commands in the file named here).
 # Measured once on the box, not live; keyed by epilogue of the <=32-row kernel.
-PMC_TRAFFIC_FILE = "profiles/c2_gemm_traffic_pmc.md"
-PMC_TRAFFIC_BYTES = {0: 101.4e6 + 0.1e6, 1: 63.9e6 + 0.03e6, 2: 181.4e6 + 0.06e6, 3: 263.3e6 + 0.1e6}
+PMC_TRAFFIC_FILE = "profiles/c2_sparse_prefill_traffic_pmc.md"
+PMC_TRAFFIC_BYTES = {0: 102.6e6 + 0.11e6, 1: 63.2e6 + 0.03e6, 2: 183.5e6 + 0.06e6, 3: 266.4e6 + 0.13e6}
 
 KIND_NAMES = {0: "qkv_rope_scatter", 1: "proj_residual", 2: "gate_up_swiglu", 3: "head_logits"}
 CLASS_NAMES = {0: "rows<=32 (decode, head)", 1: "rows>32 (prefill)"}
