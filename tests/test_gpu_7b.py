@@ -85,18 +85,25 @@ def test_7b_shape_three_layers_against_oracle(operand):
 
 def test_7b_full_depth_properties():
     """32 layers (weights drawn on the GPU; nothing here is compared with the CPU):
-    identical frames => sparse prefill equals the full recompute (cached K/V are
+    identical frames => a sparse prefill equals the recompute of every row (cached K/V are
     exactly what recomputation gives; rows are independent in every kernel, so the
-    equality is bit for bit); an empty reuse list equals the full recompute;
-    reused cache rows are untouched; 6 decoded tokens are reproducible."""
+    equality is bit for bit, whatever is reused, as long as the same GEMM kernel serves: the
+    reference is the prefill with an EMPTY reuse list, whose row count the kernels read from
+    device memory like any sparse prefill's); the full recompute proper, whose row count the
+    host knows, runs the many-rows GEMM at this size and agrees to rounding; reused cache rows
+    are untouched; 6 decoded tokens are reproducible."""
     import torch
     prev, cur, redrawn, e_prev, e_cur = inputs(seed=1)
     gm = GpuModel(CFG, seed=1, max_batch=1, max_seq=320, gain_jitter=0.1, gen_device="cuda:0")
     try:
         static = [i for i in range(N_VIS) if not redrawn[i]]
-        full = gm.prefill(e_cur[None], N_VIS)
+        host_full = gm.prefill(e_cur[None], N_VIS)
+        full = gm.prefill(e_cur[None], N_VIS, [[]])
         t_full, _ = gm.decode(1, L, 6, full["token"])
         assert np.isfinite(full["logits"]).all() and np.isfinite(full["hidden"]).all()
+        # (both are within 1.5e-2 of the oracle at this depth, tests/test_gpu_depth.py)
+        np.testing.assert_allclose(host_full["logits"], full["logits"], atol=3e-2)
+        np.testing.assert_allclose(host_full["attn_mean"], full["attn_mean"], rtol=5e-2, atol=1e-5)
         same = gm.prefill(e_cur[None], N_VIS, [static])          # same frame again, 179 reused
         np.testing.assert_array_equal(same["logits"], full["logits"])
         # (the statistic sums the same text rows in another lane order: equal up to fp32 rounding)
@@ -105,8 +112,6 @@ def test_7b_full_depth_properties():
         np.testing.assert_array_equal(same["hidden"][0][alive], full["hidden"][0][alive])
         t_same, _ = gm.decode(1, L, 6, same["token"])
         np.testing.assert_array_equal(t_same, t_full)
-        empty = gm.prefill(e_cur[None], N_VIS, [[]])
-        np.testing.assert_array_equal(empty["logits"], full["logits"])
         # ... and so does any prefix of the static set: 1 to 9 row tiles, one to three row
         # blocks (every specialisation of the GEMM main loops, their last steps included)
         for k in (256, 240, 150, 100, 40, 20):
@@ -138,7 +143,10 @@ def test_split_k_hand_over_is_reproducible():
     prev, cur, redrawn, e_prev, e_cur = inputs(seed=2)
     gm = GpuModel(CFG, seed=2, max_batch=1, max_seq=320, gain_jitter=0.1, gen_device="cuda:0")
     try:
-        full = gm.prefill(e_cur[None], N_VIS, want_stats=False, want_hidden=False)["logits"]
+        # (reference: every row recomputed with the row count read on the device, as in the loop;
+        # a stream's first prefill has to be a full one)
+        gm.prefill(e_cur[None], N_VIS, want_stats=False, want_hidden=False)
+        full = gm.prefill(e_cur[None], N_VIS, [[]], want_stats=False, want_hidden=False)["logits"]
         assert np.isfinite(full).all()
         for it in range(50):
             for k in (256, 240, 179, 150, 100, 40, 20, 0):
