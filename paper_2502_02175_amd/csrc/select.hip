@@ -118,7 +118,15 @@ __device__ inline Frac sim_fraction(uint32_t dot, uint32_t na, uint32_t nb) {
 #define SEL_MAX_LV 4096
 struct LayerMask { uint32_t w[16]; };  // bit l set = layer l is averaged over (<= 512 layers)
 
-// grid (ceil(L_v / 256), B).  flags[b, i] = 1 iff patch i is in P_final.
+// grid (ceil(L_v / 16), B).  flags[b, i] = 1 iff patch i is in P_final.
+// A workgroup ranks 256 / SEL_LPT patches, SEL_LPT lanes to a patch: every lane counts, over
+// its share of the other patches, those that come before its patch (by similarity for Top-k,
+// by score for the relevance quantile), and the counts are added up across the lanes
+// (integers: the result does not depend on how the patches are dealt).  Every workgroup
+// first builds the stream's similarities and scores in LDS, so many lanes per patch pay
+// while the launch is small (16 lanes: 8 us instead of 46 us at one stream of 256 patches)
+// and one lane per patch is right once the streams alone fill the chip.
+template <int SEL_LPT>
 __global__ __launch_bounds__(256) void select_rank_kernel(
     const uint32_t* __restrict__ terms, int L_v, uint64_t tn2, uint64_t td2, int top_k,
     const float* __restrict__ attn_mean, int n_layers, int B, LayerMask layer_mask, int n_rel, uint8_t* __restrict__ flags, float* __restrict__ relevance) {
@@ -144,16 +152,19 @@ __global__ __launch_bounds__(256) void select_rank_kernel(
     score[j] = s;
   }
   __syncthreads();
-  const int i = blockIdx.x * 256 + tid;
-  if (i >= L_v) return;
-  bool keep = pass[i] && top_k > 0;
-  if (keep) {
+  constexpr int SEL_PPW = 256 / SEL_LPT;
+  const int sub = tid % SEL_LPT;
+  const int i = blockIdx.x * SEL_PPW + tid / SEL_LPT;
+  const bool live = i < L_v;           // (a patch's 16 lanes lie in one wave and leave together)
+  const int ii = live ? i : 0;
+  const bool passed = pass[ii] && top_k > 0;
+  int rank = 0, rr = 0;
+  if (passed) {
     // rank among the passers: higher similarity first, ties -> lower index
-    const double ai = approx[i];
-    const Frac fi = sim_fraction(t[i * 3], t[i * 3 + 1], t[i * 3 + 2]);
-    int rank = 0;
-    for (int j = 0; j < L_v; ++j) {
-      if (!pass[j] || j == i) continue;
+    const double ai = approx[ii];
+    const Frac fi = sim_fraction(t[ii * 3], t[ii * 3 + 1], t[ii * 3 + 2]);
+    for (int j = sub; j < L_v; j += SEL_LPT) {
+      if (!pass[j] || j == ii) continue;
       const double dlt = approx[j] - ai;
       bool beats;
       if (dlt > 1e-12) beats = true;
@@ -161,19 +172,25 @@ __global__ __launch_bounds__(256) void select_rank_kernel(
       else {  // too close for fp64: exact cross-multiplication
         const Frac fj = sim_fraction(t[j * 3], t[j * 3 + 1], t[j * 3 + 2]);
         const u128 lhs = (u128)fj.num * fi.den, rhs = (u128)fi.num * fj.den;
-        beats = lhs > rhs || (lhs == rhs && j < i);
+        beats = lhs > rhs || (lhs == rhs && j < ii);
       }
       rank += beats;
     }
-    keep = rank < top_k;
   }
+  const float si = score[ii];
+  if (attn_mean && n_rel > 0) {
+    // rank by score descending, ties -> lower index
+    for (int j = sub; j < L_v; j += SEL_LPT) rr += (score[j] > si) || (score[j] == si && j < ii);
+  }
+#pragma unroll
+  for (int o = SEL_LPT / 2; o > 0; o >>= 1) {
+    rank += __shfl_xor(rank, o);
+    rr += __shfl_xor(rr, o);
+  }
+  if (!live || sub != 0) return;
+  bool keep = passed && rank < top_k;
   if (attn_mean) {
-    const float si = score[i];
-    if (keep && n_rel > 0) {
-      int rr = 0;  // rank by score descending, ties -> lower index
-      for (int j = 0; j < L_v; ++j) rr += (score[j] > si) || (score[j] == si && j < i);
-      keep = rr >= n_rel;
-    }
+    if (keep && n_rel > 0) keep = rr >= n_rel;
     relevance[(size_t)b * L_v + i] = si;
   } else {
     relevance[(size_t)b * L_v + i] = 0.f;
@@ -245,9 +262,14 @@ void launch_select(const uint32_t* terms, int B, int L_v, int tau_num, int tau_d
   for (int i = 0; i < 16; ++i) lm.w[i] = 0;
   for (int l = 0; l < n_layers && l < 512; ++l)
     if (!layer_mask_host || layer_mask_host[l]) lm.w[l >> 5] |= 1u << (l & 31);
-  hipLaunchKernelGGL(select_rank_kernel, dim3((L_v + 255) / 256, B), dim3(256), 0, st, terms, L_v,
-                     tn2, td2, top_k, attn_mean, n_layers, B, lm, n_rel, flags,
-                     relevance_ws);
+  const long long patches = (long long)B * L_v;
+#define VLAC_RANK(LPT_)                                                                            \
+  hipLaunchKernelGGL(select_rank_kernel<LPT_>, dim3((L_v * LPT_ + 255) / 256, B), dim3(256), 0, st, \
+                     terms, L_v, tn2, td2, top_k, attn_mean, n_layers, B, lm, n_rel, flags, relevance_ws)
+  if (patches <= 16384) VLAC_RANK(16);
+  else if (patches <= 65536) VLAC_RANK(4);
+  else VLAC_RANK(1);
+#undef VLAC_RANK
   hipLaunchKernelGGL(select_compact_kernel, dim3(B), dim3(256), 0, st, flags, relevance_ws, L_v,
                      out_idx, out_order, out_count, out_relevance, stride);
 }
@@ -258,14 +280,14 @@ void launch_select(const uint32_t* terms, int B, int L_v, int tau_num, int tau_d
 // ---------------------------------------------------------------------------
 #define RATIO_MAX_LAYERS 512
 
-__global__ __launch_bounds__(256) void layer_ratio_kernel(
+__global__ __launch_bounds__(1024) void layer_ratio_kernel(
     const float* __restrict__ attn_mean, int n_layers, int B, int L_v, float gain_k,
     const int32_t* __restrict__ reuse_count, float* __restrict__ out_alpha,
     int32_t* __restrict__ out_layer_count) {
   __shared__ double ent[RATIO_MAX_LAYERS];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  // a wave per layer (layers w, w + 4, ...): its sums are shuffle trees of fixed shape
-  for (int l = w; l < n_layers; l += 4) {
+  // a wave per layer (layers w, w + 16, ...): its sums are shuffle trees of fixed shape
+  for (int l = w; l < n_layers; l += 16) {
     const float* a = attn_mean + ((size_t)l * B + b) * L_v;
     double s = 0;
     for (int v = lane; v < L_v; v += 64) s += (double)a[v];
@@ -300,7 +322,7 @@ __global__ __launch_bounds__(256) void layer_ratio_kernel(
 void launch_layer_ratio(const float* attn_mean, int n_layers, int B, int L_v, float gain_k,
                         const int32_t* reuse_count, float* out_alpha, int32_t* out_layer_count,
                         hipStream_t st) {
-  hipLaunchKernelGGL(layer_ratio_kernel, dim3(B), dim3(256), 0, st, attn_mean, n_layers, B, L_v,
+  hipLaunchKernelGGL(layer_ratio_kernel, dim3(B), dim3(1024), 0, st, attn_mean, n_layers, B, L_v,
                      gain_k, reuse_count, out_alpha, out_layer_count);
 }
 

@@ -168,3 +168,54 @@ def test_layer_ratio_matches_oracle(gpu):
                     assert lc[b, l] == want_m[l]
                 else:
                     assert abs(int(lc[b, l]) - want_m[l]) <= 1
+
+
+@pytest.mark.parametrize("B", [4, 96, 320])
+def test_select_with_filter_at_every_launch_shape_of_the_ranking(B):
+    """The ranking kernel deals 16, 4 or 1 lanes to a patch by the number of patches in the
+    call (here 1024, 24576 and 81920 patches of 224 x 224 frames); the sets and the reuse
+    order are integer work and must not depend on that.  The oracle runs on 6 of the streams
+    (all of them at B = 4)."""
+    import torch
+    import paper_2502_02175_amd as V
+    H, p, k, nl, L_v = 224, 14, 180, 4, 256
+    ctx = V.vlac_create(V.ModelCfg(nl, 256, 4, 4, 64, 688, 256, 1e-6, 1e4, B, 32, V.OPERAND_F16))
+    try:
+        rng = np.random.default_rng(70 + B)
+        pairs = [synth.frame_pair(H, H, p, 40 + 3 * (b % 20), seed=700 + b)[:2] for b in range(min(B, 24))]
+        prev = np.stack([pairs[b % len(pairs)][0] for b in range(B)])
+        cur = np.stack([pairs[(b * 7 + 3) % len(pairs)][1] if b % 5 == 4 else pairs[b % len(pairs)][1]
+                        for b in range(B)])                     # every fifth stream: an unrelated frame pair
+        attn = (rng.random((nl, B, L_v)) ** 2).astype(np.float32)
+        attn[:, :, 17] = attn[:, :, 200]                         # tied scores in every stream
+        idx, order, rel = run_select(dict(V=V, torch=torch, ctx=ctx), prev, cur, p, 249, 250, k, attn, None, 0.6)
+        sample = range(B) if B <= 6 else [0, 4, B // 3, B // 2 + 1, B - 2, B - 1]
+        for b in sample:
+            s = O.task_relevance(attn[:, b], None)
+            np.testing.assert_array_equal(rel[b], s)
+            want, want_order = O.filter_task_relevant(O.select_static(prev[b], cur[b], p, 249, 250, k), s, 0.6)
+            assert idx[b] == want and order[b] == want_order, b
+    finally:
+        V.vlac_destroy(ctx)
+
+
+def test_layer_ratio_with_more_layers_than_waves():
+    """40 layers on the 16 waves of the ratio kernel's workgroup (layers w, w + 16, w + 32)."""
+    import torch
+    import paper_2502_02175_amd as V
+    nl, B, L_v = 40, 2, 256
+    ctx = V.vlac_create(V.ModelCfg(nl, 256, 4, 4, 64, 688, 256, 1e-6, 1e4, B, 32, V.OPERAND_F16))
+    try:
+        rng = np.random.default_rng(8)
+        attn = (rng.random((nl, B, L_v)) ** (1 + 0.2 * np.arange(nl))[:, None, None]).astype(np.float32)
+        alpha = torch.empty((B, nl), device="cuda")
+        lc = torch.empty((B, nl), dtype=torch.int32, device="cuda")
+        V.vlac_layer_ratio(ctx, torch.tensor(attn, device="cuda"), B, L_v, 0.8,
+                           torch.tensor(np.array([150, 31], dtype=np.int32), device="cuda"), alpha, lc)
+        torch.cuda.synchronize()
+        for b in range(B):
+            want = O.layer_ratio(attn[:, b], 0.8)
+            np.testing.assert_allclose(alpha[b].cpu().numpy(), want, atol=1e-6)
+            assert np.all(np.diff(lc[b].cpu().numpy()) >= 0)
+    finally:
+        V.vlac_destroy(ctx)
