@@ -115,7 +115,9 @@ size_t vlac_kv_cache_bytes(const vlac_model_cfg* cfg);
  * many-rows GEMM) cuts its work for a given row count; the kernels decide this on the
  * device, this is the same rule for inspection and tests.  out_features x k is the weight
  * matrix, rows the recomputed rows of the launch, max_splits the most K parts the
- * projection may use (1 unless it adds to the residual stream; at most 3).
+ * projection may use (1 unless it adds to the residual stream; 1, 2, 3, 4, 6 or 8 parts are
+ * considered, values above 8 count as 8; the library passes how many partial-row sets of the
+ * call's row capacity its workspace holds: 8 up to 1024 rows, 3 beyond).
  * Results: rows per work item (256, 192 or 128; a work item is 256 features wide), K parts,
  * work items (weight tiles x parts x row blocks).  Needs neither a context nor a GPU.
  * VLAC_E_NULL / VLAC_E_RANGE on null pointers or non-positive sizes. */

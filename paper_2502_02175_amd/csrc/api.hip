@@ -144,7 +144,7 @@ int vlac_create(const vlac_model_cfg* cfg, vlac_ctx** out) {
   ctx->partial_floats = (size_t)64 << 20;  // 256 MiB of split-K workspace
   // partial rows of the projection + residual GEMMs: up to 8 splits of up to 1024 rows
   ctx->rpart_floats = (size_t)8 * (mr < 1024 ? mr : 1024) * m.d_model;
-  // (many rows: up to 3 splits of all rows)
+  // (more rows: 3 splits of all rows)
   if (mr >= 1024 && (size_t)3 * mr * m.d_model > ctx->rpart_floats) ctx->rpart_floats = (size_t)3 * mr * m.d_model;
   ctx->n_counters = 1 << 16;
   ctx->stat_tt = ms / 32 + 1;

@@ -287,7 +287,7 @@ __host__ __device__ inline TallPlan tall_plan(int tiles, int n_rows, int S_max, 
   p.rt = 4;
   p.S = 1;
   p.row_blocks = (n_rows + 255) >> 8;
-  if (S_max > 3) S_max = 3;
+  if (S_max > 8) S_max = 8;
   if (S_max < 1 || KS < 24) S_max = 1;
   if (KS > 8192) KS = 8192;  // (keeps the estimate inside 32 bits; the choice no longer depends on K there)
   unsigned best = 0xffffffffu;
@@ -308,6 +308,9 @@ __host__ __device__ inline TallPlan tall_plan(int tiles, int n_rows, int S_max, 
   VLAC_TALL_TRY(1, 4) VLAC_TALL_TRY(1, 3) VLAC_TALL_TRY(1, 2)
   VLAC_TALL_TRY(2, 4) VLAC_TALL_TRY(2, 3) VLAC_TALL_TRY(2, 2)
   VLAC_TALL_TRY(3, 4) VLAC_TALL_TRY(3, 3) VLAC_TALL_TRY(3, 2)
+  VLAC_TALL_TRY(4, 4) VLAC_TALL_TRY(4, 3) VLAC_TALL_TRY(4, 2)
+  VLAC_TALL_TRY(6, 4) VLAC_TALL_TRY(6, 3) VLAC_TALL_TRY(6, 2)
+  VLAC_TALL_TRY(8, 4) VLAC_TALL_TRY(8, 3) VLAC_TALL_TRY(8, 2)
 #undef VLAC_TALL_TRY
   return p;
 }

@@ -605,7 +605,8 @@ static bool use_tall(const vlac_ctx* c, int rows_cap, int n_rows_host = -1) {
 // of fp32 per row in the workspace, and the row kernel that keeps a row in registers)
 static int tall_resid_smax(const vlac_ctx* c, int epi, int rows_cap, int d_model) {
   if (epi != EPI_RESID || d_model > 8192) return 1;
-  return (size_t)3 * rows_cap * d_model <= c->rpart_floats ? 3 : 1;
+  const size_t fit = c->rpart_floats / ((size_t)rows_cap * d_model);
+  return fit >= 8 ? 8 : fit >= 3 ? (int)fit : 1;
 }
 
 // Split factor of the one-stream kernel (row blocks of 128 rows, MB of them in the grid).

@@ -41,9 +41,22 @@ def test_few_items_are_cut_finer():
     assert PLAN(1536, 1024, 3584, 3) == (128, 1, 168)
 
 
+def test_up_to_eight_parts_where_the_workspace_allows():
+    # the parts tried are 1, 2, 3, 4, 6 and 8.  4096 x 4096 at 446 rows: 4 blocks of 128 rows x
+    # 16 tiles x 4 parts = 256 items x (24 x 32 + 512) = 1280 KiB in one round; 3 parts: 192
+    # items x 1544; 8 parts of 256-row items: 256 items x (32 x 16 + 1024) = 1536
+    assert PLAN(4096, 4096, 446, 8) == (128, 4, 256)
+    # 4096 x 11008 (344 steps) at 344 rows: 2 blocks of 192 rows x 16 tiles x 8 parts = 256 items
+    # x (28 x 43 + 768) = 1972 KiB; 256-row items in 8 parts: 32 x 43 + 1024 = 2400; 128-row
+    # items: 3 blocks, 4 parts, 192 items x (24 x 86 + 512) = 2576
+    assert PLAN(4096, 11008, 344, 8) == (192, 8, 256)
+    # a limit of 5 admits 1, 2, 3 and 4
+    assert PLAN(4096, 11008, 344, 5) == (128, 4, 192)
+
+
 @pytest.mark.parametrize("n", [1536, 2048, 4096, 12288, 17920, 22016])
 @pytest.mark.parametrize("k", [1024, 1536, 4096, 8960, 11008])
-@pytest.mark.parametrize("smax", [1, 3])
+@pytest.mark.parametrize("smax", [1, 3, 8])
 def test_invariants_over_row_counts(n, k, smax):
     tiles = -(-n // 256)
     for rows in list(range(1, 700, 37)) + list(range(700, 9000, 411)):
@@ -53,10 +66,10 @@ def test_invariants_over_row_counts(n, k, smax):
         if s > 1:
             assert k >= 1536
         # never more rounds of 256 items than the plainest cut (256-row items, unsplit) would take
-        # at a higher cost per item: the chosen estimate is the least of the nine
+        # at a higher cost per item: the chosen estimate is the least of those tried
         steps = lambda S: -(-2 * (-(-k // 64)) // S)
         cost = lambda b, S: -(-(tiles * S * -(-rows // b)) // 256) * (2 * (8 + b // 32) * steps(S) + (4 * b if S > 1 else 0))
-        assert cost(block, s) == min(cost(b, S) for b in (128, 192, 256) for S in range(1, (smax if k >= 1536 else 1) + 1))
+        assert cost(block, s) == min(cost(b, S) for b in (128, 192, 256) for S in (1, 2, 3, 4, 6, 8) if S <= (smax if k >= 1536 else 1))
 
 
 def test_bad_arguments():
