@@ -594,8 +594,9 @@ bool gemm_can_fuse_norm(int n_rows_host, int decode_pos, int kpad) {
 static const int kTallRows = 512;
 // (A launch whose row count is known on the host, a full recompute, goes by that count: from
 // kTallKnownRows rows on the many-rows kernel reads the weights once where the one-stream kernel
-// fetches them per block of 128 rows: 288 rows of one 7B stream, 32 layers: 8.2 against 9.4 ms.)
-static const int kTallKnownRows = 256;
+// fetches them per block of 128 rows: 288 rows of one 7B stream, 32 layers: 8.1 against 9.3 ms;
+// 256 rows, two blocks: 7.65 against 7.25 ms, the one-stream kernel keeps them.)
+static const int kTallKnownRows = 257;
 static bool use_tall(const vlac_ctx* c, int rows_cap, int n_rows_host = -1) {
   if (c->w8) return rows_cap >= 1024 && c->wdeq;
   return rows_cap >= kTallRows || (n_rows_host >= kTallKnownRows && rows_cap > 32);
@@ -641,7 +642,7 @@ static int rows_kernel_splits(const vlac_ctx* c, int epi, int n_blocks, int KS, 
 // so from a capacity of 768 rows on the second launch would mostly be the idle one; and
 // where the reuse lists are too short to leave fewer than kSmallRows rows (top-k 100 of two
 // camera views), only the many-rows kernel is launched.
-static const int kSmallRows = 256;
+static const int kSmallRows = 257;
 // (Rows longer than 8192 elements: the row kernel that adds the partial rows up there takes a
 // fixed split factor, so the choice between two kernels with different factors is not offered.)
 static bool use_both(const vlac_ctx* c, int rows_cap, int n_rows_host) {
